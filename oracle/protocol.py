@@ -1,0 +1,315 @@
+"""Event-driven run of Hop's queue protocol (oracle side, integers only).
+
+TEST INFRASTRUCTURE ONLY - see oracle/__init__.py.
+
+What is followed, in the paper's notation:
+  * graph, N_in / N_out, self-loop                      Section 3.1
+  * parallel approach: Send x_k and Compute on x_k at the start of iteration k,
+    then Recv, Reduce, Apply                             Section 3.2
+  * update queues with (iter, w_id) tags                 Section 4.1, Figure
+    "Decentralized Training with Update Queue"
+  * token queues TokenQ(i->j), max_ig                    Section 4.2, Figure
+    "Decentralized Training with Token Queue"
+  * backup workers N_buw = b                             Section 4.3
+  * bounded staleness s, iter_rcv, newest-per-neighbour  Section 4.4
+  * skipping iterations                                  Section 5
+  * one queue per iteration, index iter mod #queues      Section 6.1
+  * stale updates discarded on dequeue                   Section 6.2 (a)
+
+Readings where the paper is silent or at odds with itself (each also listed in
+the repository's design notes):
+  - Time is integer ticks; a message sent at T is visible at T+1; Reduce, Apply,
+    token operations and a jump take no time.  Simultaneous events are ordered
+    by (time, ARRIVE before COMPUTE_DONE, worker, sender, tag).
+  - Token queues start with max_ig-1 tokens and get one more when iteration 0
+    is entered (the token figure), which is the "max_ig tokens" of the prose.
+  - Iterations are k = 0 .. K-1; the result is x_K.
+  - s >= 1 ("staleness mode"): per in-neighbour the newest queued tag counts; a
+    neighbour is satisfied when the newest tag ever received from it is
+    >= k - s (the prose of Section 4.4, not the do-while of its figure, which
+    would wait for a new update even when an old one is within the bound); a
+    satisfied neighbour with nothing new contributes nothing to this Reduce.
+    All neighbours are looked at in one snapshot.  Tags newer than k count.
+  - s = 0 ("exact-tag mode"): only tag k counts (update-queue and backup-worker
+    figures); tags below k are discarded, tags above k stay queued.
+  - b >= 1 together with s >= 1 (the table's "Hybrid" row has no algorithm):
+    proceed once deg - b neighbours are satisfied, take every neighbour that
+    has something new within the bound.
+  - Skipping: after Apply, behind = min over out-neighbours of Iter(j) - k0
+    (= min token count - max_ig).  If behind > trigger, jump J = min(behind,
+    max_skip, max_ig, K - k0) iterations when J >= 2 and Recv(k0+J-1) would not
+    block; otherwise advance normally.  The jump's Reduce averages x_{k0+1}
+    with what Recv(k0+J-1) accepts, then J tokens move each way.
+  - A worker that reaches iteration K still inserts its tokens, sends nothing.
+
+Versions live in a ring of D slots per worker, slot = version mod D, with
+D = max_ig + 1 in staleness mode (the paper's #queues) and max_ig + 2 in
+exact-tag mode (the ring also holds the not yet sent x_{k+1}).
+"""
+import heapq
+from collections import deque
+
+import numpy as np
+
+from . import rng
+from .arith import reduce_weights
+
+STEP = 0
+JUMP = 1
+
+EV_ARRIVE = 0
+EV_DONE = 1
+
+COMPUTING = 0
+WAIT_RECV = 1
+WAIT_TOKEN = 2
+FINISHED = 3
+
+LAT = 1
+
+
+class ProtocolError(Exception):
+    pass
+
+
+class SlotDead(ProtocolError):
+    pass
+
+
+def transpose(in_nbrs):
+    out = [[] for _ in in_nbrs]
+    for i, lst in enumerate(in_nbrs):
+        for j in lst:
+            out[j].append(i)
+    return [sorted(o) for o in out]
+
+
+def shortest_paths(out_nbrs):
+    """dist[a][b] = length of the shortest directed path a -> b (inf if none)."""
+    n = len(out_nbrs)
+    dist = [[float("inf")] * n for _ in range(n)]
+    for a in range(n):
+        dist[a][a] = 0
+        dq = deque([a])
+        while dq:
+            u = dq.popleft()
+            for v in out_nbrs[u]:
+                if dist[a][v] == float("inf"):
+                    dist[a][v] = dist[a][u] + 1
+                    dq.append(v)
+    return dist
+
+
+def ring_depth(s, max_ig):
+    return max_ig + 1 if s >= 1 else max_ig + 2
+
+
+class Record:
+    __slots__ = ("seq", "kind", "worker", "k", "time", "src_worker", "src_tag",
+                 "src_slot", "w64", "w32", "out_slot")
+
+    def key(self):
+        return (self.kind, self.worker, self.k, tuple(self.src_worker),
+                tuple(self.src_tag), tuple(self.src_slot), self.out_slot)
+
+
+class Hop:
+    """One run of the protocol.  in_nbrs[i] lists the non-self in-neighbours of
+    i in ascending order; W[j][i] is the weight of sender j at receiver i."""
+
+    def __init__(self, in_nbrs, W, s, b, K, max_ig=0, skip_on=False, max_skip=10,
+                 trigger=1, seed=0, delay_kind=rng.DELAY_NONE, mult=None,
+                 table=None, check=True, trace=False):
+        self.N = len(in_nbrs)
+        self.in_nbrs = [sorted(l) for l in in_nbrs]
+        self.out_nbrs = transpose(self.in_nbrs)
+        self.W = np.asarray(W, dtype=np.float32)
+        self.s, self.b, self.K = int(s), int(b), int(K)
+        self.max_ig = int(max_ig) if max_ig else max(self.s, 1)
+        self.skip_on, self.max_skip, self.trigger = bool(skip_on), int(max_skip), int(trigger)
+        self.seed, self.delay_kind = int(seed), int(delay_kind)
+        self.mult = [1.0] * self.N if mult is None else [float(m) for m in mult]
+        self.table = table
+        self.D = ring_depth(self.s, self.max_ig)
+        self.check = check
+        for i in range(self.N):
+            if self.b > 0 and self.b >= len(self.in_nbrs[i]):
+                raise ProtocolError("N_buw(i) must be below |N_in(i)|")
+        self.dist = shortest_paths(self.out_nbrs) if check else None
+        self.trace = [] if trace else None
+
+    # ---- Recv -------------------------------------------------------------
+    def _recv_eval(self, i, k):
+        """Decide Recv(k, i) on a snapshot of i's queues, without side effects.
+        Returns (proceeds, [(j, tag), ...] ascending j)."""
+        s = self.s
+        satisfied = 0
+        accepted = []
+        for j in self.in_nbrs[i]:
+            q = self.queue[(j, i)]
+            if s >= 1:
+                new = max(q) if q else None
+                seen = self.iter_rcv[(j, i)]
+                if new is not None and new > seen:
+                    seen = new
+                if seen >= k - s:
+                    satisfied += 1
+                if new is not None and new >= k - s:
+                    accepted.append((j, new))
+            else:
+                if k in q:
+                    satisfied += 1
+                    accepted.append((j, k))
+        return satisfied >= len(self.in_nbrs[i]) - self.b, accepted
+
+    def _recv_commit(self, i, k):
+        for j in self.in_nbrs[i]:
+            q = self.queue[(j, i)]
+            if self.s >= 1:
+                if q:
+                    self.iter_rcv[(j, i)] = max(self.iter_rcv[(j, i)], max(q))
+                    q.clear()
+            else:
+                q[:] = [t for t in q if t > k]
+
+    # ---- records ------------------------------------------------------------
+    def _emit(self, kind, i, k_eff, k_label, self_slot, accepted, out_slot, T):
+        for (j, t) in accepted:
+            if not (t > self.written[j] - self.D):
+                raise SlotDead("version %d of worker %d already overwritten" % (t, j))
+        r = Record()
+        r.seq = len(self.records)
+        r.kind, r.worker, r.k, r.time = kind, i, k_label, T
+        r.src_worker = [i] + [j for (j, _) in accepted]
+        r.src_tag = [k_eff] + [t for (_, t) in accepted]
+        r.src_slot = [self_slot] + [t % self.D for (_, t) in accepted]
+        r.w64, r.w32 = reduce_weights(self.W, i, k_eff, self.s, r.src_worker, r.src_tag)
+        r.out_slot = out_slot
+        self.records.append(r)
+
+    # ---- iteration boundaries -------------------------------------------------
+    def _enter(self, i, k, T):
+        self.Iter[i] = k
+        for j in self.in_nbrs[i]:
+            self.tokens[(i, j)] += 1
+        if self.trace is not None:
+            self.trace.append(("enter", i, k))
+        if k >= self.K:
+            self.state[i] = FINISHED
+            self.finish_time[i] = T
+        else:
+            for j in self.out_nbrs[i]:
+                heapq.heappush(self.events, (T + LAT, EV_ARRIVE, j, i, k))
+            dur = rng.duration_ticks(self.seed, self.delay_kind, self.N, self.mult[i], i, k,
+                                     self.table)
+            if dur < rng.TICKS_NEVER:
+                heapq.heappush(self.events, (T + dur, EV_DONE, i, 0, k))
+            self.state[i] = COMPUTING
+        for j in self.in_nbrs[i]:
+            if self.state[j] == WAIT_TOKEN:
+                self._try_advance(j, T)
+
+    def _try_advance(self, i, T):
+        if all(self.tokens[(j, i)] >= 1 for j in self.out_nbrs[i]):
+            for j in self.out_nbrs[i]:
+                self.tokens[(j, i)] -= 1
+            self._enter(i, self.Iter[i] + 1, T)
+
+    def _try_recv(self, i, T):
+        k = self.Iter[i]
+        ok, accepted = self._recv_eval(i, k)
+        if not ok:
+            return
+        self._recv_commit(i, k)
+        D = self.D
+        self._emit(STEP, i, k, k, k % D, accepted, (k + 1) % D, T)
+        self.written[i] = k + 1
+        if self.trace is not None:
+            self.trace.append(("recv", i, k, tuple(accepted)))
+        k0 = k
+        if self.skip_on and self.out_nbrs[i]:
+            behind = min(self.Iter[j] for j in self.out_nbrs[i]) - k0
+            if behind > self.trigger:
+                J = min(behind, self.max_skip, self.max_ig, self.K - k0)
+                if J >= 2:
+                    kp = k0 + J
+                    ok2, acc2 = self._recv_eval(i, kp - 1)
+                    if ok2:
+                        self._recv_commit(i, kp - 1)
+                        self._emit(JUMP, i, kp - 1, kp, (k0 + 1) % D, acc2, kp % D, T)
+                        self.written[i] = kp
+                        for j in self.out_nbrs[i]:
+                            self.tokens[(j, i)] -= J
+                            assert self.tokens[(j, i)] >= 0
+                        for j in self.in_nbrs[i]:
+                            self.tokens[(i, j)] += J - 1
+                        self.n_jumps += 1
+                        if self.trace is not None:
+                            self.trace.append(("jump", i, kp, tuple(acc2)))
+                        self._enter(i, kp, T)
+                        return
+        self.state[i] = WAIT_TOKEN
+        self._try_advance(i, T)
+
+    # ---- invariants (token identity, Theorems 1 and 2, the gap table) -------
+    def _check(self):
+        N, ig = self.N, self.max_ig
+        It = self.Iter
+        for h in range(N):
+            for r in self.in_nbrs[h]:
+                t = self.tokens[(h, r)]
+                assert t == It[h] - It[r] + ig and t >= 0, "token identity broken"
+                assert t <= ig * (self.dist[h][r] + 1), "token queue over capacity"
+        for i in range(N):
+            for j in range(N):
+                if i == j:
+                    continue
+                gap = It[i] - It[j]
+                assert gap <= ig * self.dist[i][j], "token bound (Theorem 2) broken"
+                if self.b == 0:
+                    fwd = (self.s + 1) * self.dist[j][i] if self.s >= 1 else self.dist[j][i]
+                    assert gap <= fwd, "forward gap bound (gap table) broken"
+        if self.s == 0 and self.b == 0:
+            # Section 4.2's capacity bound is for standard training; with backup
+            # workers late updates pile up until the next dequeue (Section 4.3)
+            for i in range(N):
+                occ = sum(len(self.queue[(j, i)]) for j in self.in_nbrs[i])
+                assert occ <= (1 + ig) * len(self.in_nbrs[i]), "update queue over capacity"
+        self.max_gap = max(self.max_gap, max(It) - min(It))
+
+    # ---- main loop -------------------------------------------------------------
+    def run(self):
+        N = self.N
+        self.records = []
+        self.events = []
+        self.Iter = [0] * N
+        self.state = [COMPUTING] * N
+        self.finish_time = [None] * N
+        self.written = [0] * N
+        self.queue = {(j, i): [] for i in range(N) for j in self.in_nbrs[i]}
+        self.iter_rcv = {(j, i): -1 for i in range(N) for j in self.in_nbrs[i]}
+        self.tokens = {(i, j): self.max_ig - 1 for i in range(N) for j in self.in_nbrs[i]}
+        self.n_jumps = 0
+        self.max_gap = 0
+        self.max_queue = 0
+        for i in range(N):
+            self._enter(i, 0, 0)
+        if self.check:
+            self._check()
+        while self.events:
+            T, kind, a, snd, tag = heapq.heappop(self.events)
+            if kind == EV_ARRIVE:
+                self.queue[(snd, a)].append(tag)
+                self.max_queue = max(self.max_queue, len(self.queue[(snd, a)]))
+                if self.trace is not None:
+                    self.trace.append(("deliver", snd, a, tag))
+                if self.state[a] == WAIT_RECV:
+                    self._try_recv(a, T)
+            else:
+                assert self.state[a] == COMPUTING and self.Iter[a] == tag
+                self.state[a] = WAIT_RECV
+                self._try_recv(a, T)
+            if self.check:
+                self._check()
+        self.stalled = any(st != FINISHED for st in self.state)
+        return self.records
