@@ -1,0 +1,679 @@
+// C ABI of the Hop hot path: contexts, layout of the parameter rings in the caller's arena,
+// translation of a schedule into device job descriptors, and the per-wave kernel launches.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "hop_internal.h"
+
+namespace {
+
+constexpr int64_t kAlignFloats = 64;       // 256 bytes
+constexpr int kMaxBatch = 1024;
+constexpr size_t kMaxPendingEvents = 1 << 15;
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+int effective_max_ig(int s, const hop_opts* o) {
+    int ig = o ? o->max_ig : 0;
+    return ig > 0 ? ig : std::max(s, 1);
+}
+
+// Every slot starts on a 256-byte boundary; the extra 256 bytes keep the slots of a power-of-two d
+// from all mapping to the same HBM channel phase.
+int64_t slot_stride(int64_t d) { return round_up(d, kAlignFloats) + kAlignFloats; }
+
+int64_t partial_floats(int64_t d, int batch) {
+    return round_up((int64_t)std::max(batch, 1) * hopk_dense_nseg(d), kAlignFloats);
+}
+
+int hip_fail(hop_ctx* ctx, hipError_t e, const char* what) {
+    if (ctx) ctx->last_error = std::string(what) + ": " + hipGetErrorString(e);
+    std::fprintf(stderr, "libhop: %s: %s\n", what, hipGetErrorString(e));
+    return HOP_ERR_HIP;
+}
+
+#define HOP_HIP(ctx, call)                                          \
+    do {                                                            \
+        hipError_t e_ = (call);                                     \
+        if (e_ != hipSuccess) return hip_fail((ctx), e_, #call);    \
+    } while (0)
+
+#define HOP_LAUNCH(ctx, call)                                                        \
+    do {                                                                             \
+        int e_ = (call);                                                             \
+        if (e_ != 0) return hip_fail((ctx), (hipError_t)e_, "kernel launch " #call); \
+    } while (0)
+
+void free_device_side(hop_schedule* s) {
+    if (s->mix_dev) (void)hipFree(s->mix_dev);
+    if (s->grad_dev) (void)hipFree(s->grad_dev);
+    if (s->rows_dev) (void)hipFree(s->rows_dev);
+    if (s->coef_dev) (void)hipFree(s->coef_dev);
+    s->mix_dev = nullptr;
+    s->grad_dev = nullptr;
+    s->rows_dev = nullptr;
+    s->coef_dev = nullptr;
+    s->built_mode = -1;
+}
+
+float* slot_ptr(const hop_ctx* c, int worker, int slot) {
+    return c->ring + ((int64_t)worker * c->D + slot) * c->stride;
+}
+
+// Translate the schedule into device descriptors for the context's current gradient source.
+int build_jobs(hop_ctx* c, hop_schedule* s) {
+    free_device_side(s);
+    const int R = (int)s->kind.size();
+    const int mode = c->grad_mode;
+    const int B = s->batch;
+    if ((mode == HOP_GRAD_SVM_DENSE || mode == HOP_GRAD_SVM_CSR) && B <= 0) return HOP_ERR_STATE;
+    if (B > 0) {
+        HOP_HIP(c, hipMalloc((void**)&s->rows_dev, (size_t)R * B * sizeof(int32_t)));
+        HOP_HIP(c, hipMemcpy(s->rows_dev, s->batch_rows.data(), (size_t)R * B * sizeof(int32_t),
+                             hipMemcpyHostToDevice));
+        HOP_HIP(c, hipMalloc((void**)&s->coef_dev, (size_t)R * B * sizeof(float)));
+        HOP_HIP(c, hipMemset(s->coef_dev, 0, (size_t)R * B * sizeof(float)));
+    }
+    std::vector<HopMixJob> mix((size_t)std::max(R, 1));
+    std::vector<HopGradJob> grad;
+    s->grad_begin.assign(s->n_waves + 1, 0);
+    s->wave_mix_bytes.assign(s->n_waves, 0.0);
+    s->wave_grad_bytes.assign(s->n_waves, 0.0);
+    const float eta = c->opts.lr;
+    const int nseg = hopk_dense_nseg(c->d);
+    for (int w = 0; w < s->n_waves; ++w) {
+        for (int p = s->wave_begin[w]; p < s->wave_begin[w + 1]; ++p) {
+            const int e = s->wave_order[p];
+            const int i = s->worker[e];
+            HopMixJob& mj = mix[p];
+            std::memset(&mj, 0, sizeof(mj));
+            mj.out = slot_ptr(c, i, s->out_slot[e]);
+            mj.eta = eta;
+            mj.A = s->src_begin[e + 1] - s->src_begin[e];
+            for (int a = 0; a < mj.A; ++a) {
+                int q = s->src_begin[e] + a;
+                mj.src[a] = slot_ptr(c, s->src_worker[q], s->src_slot[q]);
+                mj.w[a] = s->src_weight[q];
+            }
+            const bool step = s->kind[e] == HOP_STEP;
+            if (step && mode != HOP_GRAD_ZERO) {
+                HopGradJob gj;
+                std::memset(&gj, 0, sizeof(gj));
+                gj.w = mj.src[0];
+                gj.g = c->gbuf + (int64_t)i * c->stride;
+                gj.out = mj.out;
+                if (B > 0) {
+                    gj.rows = s->rows_dev + (size_t)e * B;
+                    gj.coef = s->coef_dev + (size_t)e * B;
+                }
+                const HopData& dd = c->data[i];
+                bool want_job = true;
+                if (mode == HOP_GRAD_SVM_DENSE) {
+                    if (!dd.X || !dd.y) return HOP_ERR_STATE;
+                    gj.X = dd.X;
+                    gj.y = dd.y;
+                    gj.partial = c->partial + (int64_t)i * partial_floats(c->d, c->opts.batch);
+                    mj.g = gj.g;
+                    s->wave_grad_bytes[w] += 4.0 * ((double)B * c->d + 2.0 * c->d) + 8.0 * B;
+                } else if (mode == HOP_GRAD_SVM_CSR) {
+                    if (!dd.rowptr || !dd.col || !dd.val || !dd.y) return HOP_ERR_STATE;
+                    gj.rowptr = dd.rowptr;
+                    gj.col = dd.col;
+                    gj.val = dd.val;
+                    gj.y = dd.y;
+                    // lambda w folds into the self term: sum_a w'_a x_a - eta lambda x_self - eta (sparse part)
+                    mj.w[0] = mj.w[0] - eta * c->opts.lambda;
+                } else if (mode == HOP_GRAD_SYNTH) {
+                    hoprng::synth_keys(c->opts.seed, i, s->iter[e], &gj.k0, &gj.k1, &gj.k2);
+                    gj.scale = hoprng::synth_scale(c->synth_variance);
+                    mj.g = gj.g;
+                    s->wave_grad_bytes[w] += 4.0 * c->d;
+                } else {  // external
+                    mj.g = c->external + (int64_t)i * c->d;
+                    want_job = false;
+                }
+                if (want_job) grad.push_back(gj);
+            }
+            s->wave_mix_bytes[w] += 4.0 * (double)c->d * (mj.A + 1 + (mj.g ? 1 : 0));
+        }
+        s->grad_begin[w + 1] = (int32_t)grad.size();
+    }
+    (void)nseg;
+    if (R > 0) {
+        HOP_HIP(c, hipMalloc((void**)&s->mix_dev, (size_t)R * sizeof(HopMixJob)));
+        HOP_HIP(c, hipMemcpy(s->mix_dev, mix.data(), (size_t)R * sizeof(HopMixJob), hipMemcpyHostToDevice));
+    }
+    if (!grad.empty()) {
+        HOP_HIP(c, hipMalloc((void**)&s->grad_dev, grad.size() * sizeof(HopGradJob)));
+        HOP_HIP(c, hipMemcpy(s->grad_dev, grad.data(), grad.size() * sizeof(HopGradJob), hipMemcpyHostToDevice));
+    }
+    s->built_mode = mode;
+    s->built_epoch = c->epoch;
+    return HOP_OK;
+}
+
+// ---- profiling with HIP events on the context's stream ----
+int prof_flush(hop_ctx* c) {
+    HopProfile& p = c->prof;
+    if (p.pending_kernel.empty()) return HOP_OK;
+    HOP_HIP(c, hipStreamSynchronize((hipStream_t)c->stream));
+    for (size_t n = 0; n < p.pending_kernel.size(); ++n) {
+        float ms = 0.f;
+        HOP_HIP(c, hipEventElapsedTime(&ms, (hipEvent_t)p.ev[2 * n], (hipEvent_t)p.ev[2 * n + 1]));
+        int k = p.pending_kernel[n];
+        p.ms[k] += ms;
+        p.launches[k] += 1;
+        p.bytes[k] += p.pending_bytes[n];
+    }
+    p.pending_kernel.clear();
+    p.pending_bytes.clear();
+    return HOP_OK;
+}
+
+int prof_begin(hop_ctx* c, int kernel, double bytes) {
+    if (!c->profiling) return HOP_OK;
+    HopProfile& p = c->prof;
+    if (p.pending_kernel.size() >= kMaxPendingEvents) {
+        int rc = prof_flush(c);
+        if (rc) return rc;
+    }
+    size_t n = p.pending_kernel.size();
+    while (p.ev.size() < 2 * (n + 1)) {
+        hipEvent_t e;
+        HOP_HIP(c, hipEventCreate(&e));
+        p.ev.push_back((void*)e);
+    }
+    p.pending_kernel.push_back(kernel);
+    p.pending_bytes.push_back(bytes);
+    HOP_HIP(c, hipEventRecord((hipEvent_t)p.ev[2 * n], (hipStream_t)c->stream));
+    return HOP_OK;
+}
+
+int prof_end(hop_ctx* c) {
+    if (!c->profiling) return HOP_OK;
+    size_t n = c->prof.pending_kernel.size() - 1;
+    HOP_HIP(c, hipEventRecord((hipEvent_t)c->prof.ev[2 * n + 1], (hipStream_t)c->stream));
+    return HOP_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char* hop_strerror(int code) {
+    switch (code) {
+        case HOP_OK: return "ok";
+        case HOP_ERR_INVALID_ARG: return "invalid argument";
+        case HOP_ERR_BAD_GRAPH: return "bad communication graph";
+        case HOP_ERR_BAD_WEIGHTS: return "bad mixing weights";
+        case HOP_ERR_BAD_BACKUP: return "backup workers not below the in-degree";
+        case HOP_ERR_ARENA_TOO_SMALL: return "device arena too small";
+        case HOP_ERR_DEADLOCK: return "protocol stalled with unfinished workers";
+        case HOP_ERR_SLOT_DEAD: return "accepted version already overwritten in its ring";
+        case HOP_ERR_HIP: return "HIP runtime error";
+        case HOP_ERR_NO_DEVICE: return "context has no device memory";
+        case HOP_ERR_STATE: return "call out of order";
+        case HOP_ERR_NOMEM: return "out of host memory";
+        default: return "unknown error";
+    }
+}
+
+int hop_version(void) { return 1; }
+
+int hop_opts_default(hop_opts* o) {
+    if (!o) return HOP_ERR_INVALID_ARG;
+    std::memset(o, 0, sizeof(*o));
+    o->max_ig = 0;
+    o->skip_on = 0;
+    o->max_skip = 10;
+    o->trigger = 1;
+    o->lr = 0.01f;
+    o->lambda = 1e-4f;
+    o->batch = 0;
+    o->seed = 0;
+    return HOP_OK;
+}
+
+int hop_layout(int64_t d, int32_t s, const hop_opts* o, int32_t* depth, int64_t* stride) {
+    if (d < 1 || s < 0) return HOP_ERR_INVALID_ARG;
+    int ig = effective_max_ig(s, o);
+    if (depth) *depth = s >= 1 ? ig + 1 : ig + 2;
+    if (stride) *stride = slot_stride(d);
+    return HOP_OK;
+}
+
+size_t hop_arena_bytes(int32_t N, int64_t d, int32_t s, const hop_opts* o) {
+    int32_t D = 0;
+    int64_t stride = 0;
+    if (N < 1 || hop_layout(d, s, o, &D, &stride) != HOP_OK) return 0;
+    int batch = o ? o->batch : 0;
+    int64_t floats = (int64_t)N * D * stride + (int64_t)N * stride + (int64_t)N * partial_floats(d, batch);
+    return (size_t)floats * sizeof(float);
+}
+
+int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64_t d, int32_t s, int32_t b,
+             const hop_opts* opts, const hop_device* dev) {
+    if (!out) return HOP_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!g || !W || !g->row_ptr || N < 1 || d < 1 || d > 0xFFFFFFFFll || s < 0 || b < 0 || g->N != N)
+        return HOP_ERR_INVALID_ARG;
+    if (N > 1 && !g->col) return HOP_ERR_INVALID_ARG;
+    hop_opts o;
+    hop_opts_default(&o);
+    if (opts) o = *opts;
+    if (o.max_ig < 0 || o.max_skip < 1 || o.trigger < 0 || o.batch < 0 || o.batch > kMaxBatch)
+        return HOP_ERR_INVALID_ARG;
+    hop_ctx* c = new (std::nothrow) hop_ctx();
+    if (!c) return HOP_ERR_NOMEM;
+    c->N = N; c->d = d; c->s = s; c->b = b; c->opts = o;
+    c->max_ig = effective_max_ig(s, &o);
+    c->D = s >= 1 ? c->max_ig + 1 : c->max_ig + 2;
+    c->stride = slot_stride(d);
+    int rc = HOP_OK;
+    c->in_nbrs.assign(N, {});
+    c->out_nbrs.assign(N, {});
+    if (g->row_ptr[0] != 0) rc = HOP_ERR_BAD_GRAPH;
+    for (int i = 0; i < N && rc == HOP_OK; ++i) {
+        int lo = g->row_ptr[i], hi = g->row_ptr[i + 1];
+        if (hi < lo || hi - lo + 1 > HOP_MAX_A) { rc = HOP_ERR_BAD_GRAPH; break; }
+        for (int p = lo; p < hi; ++p) {
+            int j = g->col[p];
+            if (j < 0 || j >= N || j == i || (p > lo && j <= g->col[p - 1])) { rc = HOP_ERR_BAD_GRAPH; break; }
+            c->in_nbrs[i].push_back(j);
+        }
+    }
+    if (rc == HOP_OK) {
+        for (int i = 0; i < N; ++i)
+            for (int j : c->in_nbrs[i]) c->out_nbrs[j].push_back(i);   // ascending by construction
+        for (int i = 0; i < N; ++i)
+            if (b > 0 && b >= (int)c->in_nbrs[i].size()) rc = HOP_ERR_BAD_BACKUP;
+    }
+    if (rc == HOP_OK) {
+        c->W.assign(W, W + (size_t)N * N);
+        for (int i = 0; i < N && rc == HOP_OK; ++i) {
+            double col_sum = 0.0;
+            for (int j = 0; j < N; ++j) {
+                float v = W[(size_t)j * N + i];
+                if (!(v >= 0.f)) rc = HOP_ERR_BAD_WEIGHTS;
+                bool edge = j == i || std::binary_search(c->in_nbrs[i].begin(), c->in_nbrs[i].end(), j);
+                if (!edge && v != 0.f) rc = HOP_ERR_BAD_WEIGHTS;
+                col_sum += v;
+            }
+            if (!(W[(size_t)i * N + i] > 0.f) || std::fabs(col_sum - 1.0) > 1e-4) rc = HOP_ERR_BAD_WEIGHTS;
+        }
+    }
+    if (rc == HOP_OK && dev) {
+        size_t need = hop_arena_bytes(N, d, s, &o);
+        if (!dev->arena || ((uintptr_t)dev->arena & 255u)) rc = HOP_ERR_INVALID_ARG;
+        else if (dev->arena_bytes < need) rc = HOP_ERR_ARENA_TOO_SMALL;
+        else {
+            c->has_device = true;
+            c->arena = (char*)dev->arena;
+            c->arena_bytes = dev->arena_bytes;
+            c->stream = dev->hip_stream;
+            c->ring = (float*)dev->arena;
+            c->gbuf = c->ring + (int64_t)N * c->D * c->stride;
+            c->partial = c->gbuf + (int64_t)N * c->stride;
+        }
+    }
+    if (rc != HOP_OK) {
+        delete c;
+        return rc;
+    }
+    c->data.assign(N, HopData{});
+    c->version.assign(N, 0);
+    *out = c;
+    return HOP_OK;
+}
+
+int hop_destroy(hop_ctx* c) {
+    if (!c) return HOP_ERR_INVALID_ARG;
+    for (void* e : c->prof.ev) (void)hipEventDestroy((hipEvent_t)e);
+    delete c;
+    return HOP_OK;
+}
+
+int hop_set_params(hop_ctx* c, const float* p0, int per_worker, int on_device) {
+    if (!c || !p0) return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    hipStream_t st = (hipStream_t)c->stream;
+    for (int i = 0; i < c->N; ++i) {
+        const float* src = per_worker ? p0 + (int64_t)i * c->d : p0;
+        HOP_HIP(c, hipMemcpyAsync(slot_ptr(c, i, 0), src, (size_t)c->d * sizeof(float),
+                                  on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, st));
+    }
+    if (!on_device) HOP_HIP(c, hipStreamSynchronize(st));   // p0 is only borrowed for the call
+    std::fill(c->version.begin(), c->version.end(), 0);
+    c->running = nullptr;
+    c->next_wave = 0;
+    return HOP_OK;
+}
+
+int hop_set_rows(hop_ctx* c, int32_t worker, int64_t rows) {
+    if (!c || worker < 0 || worker >= c->N || rows < 0 || rows > 0x7FFFFFFFll) return HOP_ERR_INVALID_ARG;
+    c->data[worker] = HopData{};
+    c->data[worker].rows = rows;
+    c->epoch++;
+    return HOP_OK;
+}
+
+int hop_set_data_dense(hop_ctx* c, int32_t worker, const float* X, const float* y, int64_t rows) {
+    if (!c || worker < 0 || worker >= c->N || !X || !y || rows < 1 || rows > 0x7FFFFFFFll)
+        return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    if ((c->d % 4 == 0) && !aligned16(X)) return HOP_ERR_INVALID_ARG;
+    HopData dd;
+    dd.rows = rows;
+    dd.X = X;
+    dd.y = y;
+    c->data[worker] = dd;
+    c->epoch++;
+    return HOP_OK;
+}
+
+int hop_set_data_csr(hop_ctx* c, int32_t worker, const int64_t* rowptr, const int32_t* col, const float* val,
+                     const float* y, int64_t rows) {
+    if (!c || worker < 0 || worker >= c->N || !rowptr || !col || !val || !y || rows < 1 || rows > 0x7FFFFFFFll)
+        return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    HopData dd;
+    dd.rows = rows;
+    dd.rowptr = rowptr;
+    dd.col = col;
+    dd.val = val;
+    dd.y = y;
+    c->data[worker] = dd;
+    c->epoch++;
+    return HOP_OK;
+}
+
+int hop_set_grad_source(hop_ctx* c, int mode, float variance, const float* external) {
+    if (!c || mode < HOP_GRAD_ZERO || mode > HOP_GRAD_EXTERNAL) return HOP_ERR_INVALID_ARG;
+    if (mode == HOP_GRAD_SYNTH && !(variance >= 0.f)) return HOP_ERR_INVALID_ARG;
+    if (mode == HOP_GRAD_EXTERNAL && (!external || !aligned16(external) || (c->d % 4 != 0 && c->N > 1)))
+        return HOP_ERR_INVALID_ARG;
+    c->grad_mode = mode;
+    c->synth_variance = variance;
+    c->external = external;
+    c->epoch++;
+    return HOP_OK;
+}
+
+int hop_simulate(hop_ctx* c, const hop_delay_model* dm, int32_t max_iter, hop_schedule** out) {
+    if (!c || !out || max_iter < 0) return HOP_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (dm) {
+        if (dm->kind < HOP_DELAY_NONE || dm->kind > HOP_DELAY_TABLE) return HOP_ERR_INVALID_ARG;
+        if (dm->kind == HOP_DELAY_TABLE && (!dm->table || dm->table_iters < max_iter)) return HOP_ERR_INVALID_ARG;
+    }
+    hop_schedule* s = new (std::nothrow) hop_schedule();
+    if (!s) return HOP_ERR_NOMEM;
+    int rc;
+    try {
+        rc = hop_run_protocol(c, dm, max_iter, s);
+    } catch (const std::bad_alloc&) {
+        rc = HOP_ERR_NOMEM;
+    }
+    if (rc != HOP_OK && rc != HOP_ERR_DEADLOCK) {
+        delete s;
+        return rc;
+    }
+    s->owner = c;
+    *out = s;
+    return rc;
+}
+
+int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* v) {
+    if (!s || !v) return HOP_ERR_INVALID_ARG;
+    std::memset(v, 0, sizeof(*v));
+    v->n_records = (int32_t)s->kind.size();
+    v->n_sources = (int32_t)s->src_worker.size();
+    v->n_waves = s->n_waves;
+    v->n_workers = s->N;
+    v->depth = s->D;
+    v->batch = s->batch;
+    v->stalled = s->stalled;
+    v->n_jumps = s->n_jumps;
+    v->kind = s->kind.data();
+    v->worker = s->worker.data();
+    v->iter = s->iter.data();
+    v->time = s->time.data();
+    v->wave = s->wave.data();
+    v->out_slot = s->out_slot.data();
+    v->src_begin = s->src_begin.data();
+    v->src_worker = s->src_worker.data();
+    v->src_tag = s->src_tag.data();
+    v->src_slot = s->src_slot.data();
+    v->src_weight = s->src_weight.data();
+    v->batch_rows = s->batch > 0 ? s->batch_rows.data() : nullptr;
+    v->final_iter = s->final_iter.data();
+    v->finish_time = s->finish_time.data();
+    v->wave_begin = s->wave_begin.data();
+    v->wave_order = s->wave_order.data();
+    return HOP_OK;
+}
+
+int hop_schedule_free(hop_schedule* s) {
+    if (!s) return HOP_ERR_INVALID_ARG;
+    free_device_side(s);
+    delete s;
+    return HOP_OK;
+}
+
+int hop_step(hop_ctx* c, const hop_schedule* sched, int32_t wave_begin, int32_t wave_end) {
+    if (!c || !sched) return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    hop_schedule* s = const_cast<hop_schedule*>(sched);
+    if (s->owner != c) return HOP_ERR_INVALID_ARG;
+    if (wave_end < 0) wave_end = s->n_waves;
+    if (wave_begin < 0 || wave_begin > wave_end || wave_end > s->n_waves) return HOP_ERR_INVALID_ARG;
+    if (wave_begin != 0 && (c->running != s || wave_begin != c->next_wave)) return HOP_ERR_STATE;
+    if (s->built_mode != c->grad_mode || s->built_epoch != c->epoch) {
+        int rc = build_jobs(c, s);
+        if (rc != HOP_OK) return rc;
+    }
+    c->running = s;
+    const int B = s->batch;
+    const int mode = c->grad_mode;
+    for (int w = wave_begin; w < wave_end; ++w) {
+        const int jb = s->wave_begin[w], nj = s->wave_begin[w + 1] - jb;
+        const int gb = s->grad_begin[w], ng = s->grad_begin[w + 1] - gb;
+        const HopGradJob* gj = s->grad_dev ? s->grad_dev + gb : nullptr;
+        int rc;
+        if (ng > 0 && mode == HOP_GRAD_SYNTH) {
+            if ((rc = prof_begin(c, HOP_KERNEL_SYNTH, s->wave_grad_bytes[w]))) return rc;
+            HOP_LAUNCH(c, hopk_synth(gj, ng, c->d, c->stream));
+            if ((rc = prof_end(c))) return rc;
+        } else if (ng > 0 && mode == HOP_GRAD_SVM_DENSE) {
+            if ((rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
+            HOP_LAUNCH(c, hopk_dense_margin(gj, ng, B, c->d, c->stream));
+            HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, c->stream));
+            if ((rc = prof_end(c))) return rc;
+        } else if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
+            if ((rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
+            HOP_LAUNCH(c, hopk_csr_margin(gj, ng, B, c->stream));
+            if ((rc = prof_end(c))) return rc;
+        }
+        if ((rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
+        HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, c->stream));
+        if ((rc = prof_end(c))) return rc;
+        if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
+            if ((rc = prof_begin(c, HOP_KERNEL_GRAD, 0.0))) return rc;
+            HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, c->opts.lr, c->stream));
+            if ((rc = prof_end(c))) return rc;
+        }
+        for (int p = jb; p < jb + nj; ++p) {
+            int e = s->wave_order[p];
+            c->version[s->worker[e]] = s->kind[e] == HOP_STEP ? s->iter[e] + 1 : s->iter[e];
+        }
+        c->next_wave = w + 1;
+    }
+    return HOP_OK;
+}
+
+int hop_params(hop_ctx* c, int32_t worker, const float** dev_ptr, int32_t* iter) {
+    if (!c || worker < 0 || worker >= c->N) return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    if (dev_ptr) *dev_ptr = slot_ptr(c, worker, c->version[worker] % c->D);
+    if (iter) *iter = c->version[worker];
+    return HOP_OK;
+}
+
+int hop_slot(hop_ctx* c, int32_t worker, int32_t slot, float** dev_ptr) {
+    if (!c || !dev_ptr || worker < 0 || worker >= c->N || slot < 0 || slot >= c->D) return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    *dev_ptr = slot_ptr(c, worker, slot);
+    return HOP_OK;
+}
+
+int hop_coef(hop_ctx* c, const hop_schedule* s, int32_t record, const float** dev_ptr) {
+    if (!c || !s || !dev_ptr || record < 0 || record >= (int)s->kind.size()) return HOP_ERR_INVALID_ARG;
+    if (!s->coef_dev || s->batch <= 0) return HOP_ERR_STATE;
+    *dev_ptr = s->coef_dev + (size_t)record * s->batch;
+    return HOP_OK;
+}
+
+int hop_profile(hop_ctx* c, int enable) {
+    if (!c) return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    if (!enable && c->profiling) {
+        int rc = prof_flush(c);
+        if (rc) return rc;
+    }
+    c->profiling = enable != 0;
+    return HOP_OK;
+}
+
+int hop_profile_read(hop_ctx* c, int kernel, double* ms, int64_t* launches, double* bytes) {
+    if (!c || kernel < 0 || kernel >= HOP_KERNEL_COUNT) return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    int rc = prof_flush(c);
+    if (rc) return rc;
+    if (ms) *ms = c->prof.ms[kernel];
+    if (launches) *launches = c->prof.launches[kernel];
+    if (bytes) *bytes = c->prof.bytes[kernel];
+    c->prof.ms[kernel] = 0;
+    c->prof.launches[kernel] = 0;
+    c->prof.bytes[kernel] = 0;
+    return HOP_OK;
+}
+
+// ---- stand-alone kernels: upload one descriptor set, launch, wait, release ----
+int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* stream) {
+    if (!jobs || n_jobs < 0 || d < 1) return HOP_ERR_INVALID_ARG;
+    if (n_jobs == 0) return HOP_OK;
+    std::vector<HopMixJob> host((size_t)n_jobs);
+    for (int j = 0; j < n_jobs; ++j) {
+        const hop_mix_job& in = jobs[j];
+        if (in.A < 1 || in.A > HOP_MAX_A || !in.out || !aligned16(in.out) || (in.g && !aligned16(in.g)))
+            return HOP_ERR_INVALID_ARG;
+        HopMixJob& mj = host[j];
+        std::memset(&mj, 0, sizeof(mj));
+        mj.out = in.out;
+        mj.g = in.g;
+        mj.eta = in.eta;
+        mj.A = in.A;
+        for (int a = 0; a < in.A; ++a) {
+            if (!in.src[a] || !aligned16(in.src[a])) return HOP_ERR_INVALID_ARG;
+            mj.src[a] = in.src[a];
+            mj.w[a] = in.w[a];
+        }
+    }
+    HopMixJob* dev = nullptr;
+    HOP_HIP(nullptr, hipMalloc((void**)&dev, host.size() * sizeof(HopMixJob)));
+    hipError_t e = hipMemcpy(dev, host.data(), host.size() * sizeof(HopMixJob), hipMemcpyHostToDevice);
+    int rc = 0;
+    if (e == hipSuccess) rc = hopk_mix(dev, n_jobs, d, stream);
+    hipError_t e2 = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(dev);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "hipMemcpy");
+    if (rc) return hip_fail(nullptr, (hipError_t)rc, "mix launch");
+    if (e2 != hipSuccess) return hip_fail(nullptr, e2, "hipStreamSynchronize");
+    return HOP_OK;
+}
+
+int64_t hop_grad_scratch_floats(int64_t d, int32_t B) {
+    if (d < 1 || B < 1) return 0;
+    return partial_floats(d, B);
+}
+
+static int run_one_grad(const HopGradJob& gj, int kind, int B, int64_t d, float lambda, void* stream) {
+    HopGradJob* dev = nullptr;
+    HOP_HIP(nullptr, hipMalloc((void**)&dev, sizeof(HopGradJob)));
+    hipError_t e = hipMemcpy(dev, &gj, sizeof(HopGradJob), hipMemcpyHostToDevice);
+    int rc = 0;
+    if (e == hipSuccess) {
+        if (kind == HOP_GRAD_SVM_DENSE) {
+            rc = hopk_dense_margin(dev, 1, B, d, stream);
+            if (!rc) rc = hopk_dense_grad(dev, 1, B, d, lambda, stream);
+        } else if (kind == HOP_GRAD_SVM_CSR) {
+            rc = hopk_csr_margin(dev, 1, B, stream);
+            if (!rc) rc = hopk_csr_dense_grad(dev, 1, B, d, lambda, stream);
+        } else {
+            rc = hopk_synth(dev, 1, d, stream);
+        }
+    }
+    hipError_t e2 = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(dev);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "hipMemcpy");
+    if (rc) return hip_fail(nullptr, (hipError_t)rc, "gradient launch");
+    if (e2 != hipSuccess) return hip_fail(nullptr, e2, "hipStreamSynchronize");
+    return HOP_OK;
+}
+
+int hop_svm_grad_dense(const float* X, const float* y, const float* w, const int32_t* rows_dev, int32_t B,
+                       int64_t d, float lambda, float* g, float* coef, float* scratch, void* stream) {
+    if (!X || !y || !w || !rows_dev || !g || !coef || !scratch || B < 1 || B > kMaxBatch || d < 1)
+        return HOP_ERR_INVALID_ARG;
+    if (d % 4 == 0 && (!aligned16(X) || !aligned16(w) || !aligned16(g))) return HOP_ERR_INVALID_ARG;
+    HopGradJob gj;
+    std::memset(&gj, 0, sizeof(gj));
+    gj.X = X; gj.y = y; gj.w = w; gj.rows = rows_dev; gj.g = g; gj.coef = coef; gj.partial = scratch;
+    return run_one_grad(gj, HOP_GRAD_SVM_DENSE, B, d, lambda, stream);
+}
+
+int hop_svm_grad_csr(const int64_t* rowptr, const int32_t* col, const float* val, const float* y, const float* w,
+                     const int32_t* rows_dev, int32_t B, int64_t d, float lambda, float* g, float* coef,
+                     void* stream) {
+    if (!rowptr || !col || !val || !y || !w || !rows_dev || !g || !coef || B < 1 || B > kMaxBatch || d < 1)
+        return HOP_ERR_INVALID_ARG;
+    HopGradJob gj;
+    std::memset(&gj, 0, sizeof(gj));
+    gj.rowptr = rowptr; gj.col = col; gj.val = val; gj.y = y; gj.w = w; gj.rows = rows_dev;
+    gj.g = g; gj.out = g; gj.coef = coef;
+    return run_one_grad(gj, HOP_GRAD_SVM_CSR, B, d, lambda, stream);
+}
+
+int hop_synth_grad(uint64_t seed, int32_t worker, int32_t iter, float variance, float* g, int64_t d, void* stream) {
+    if (!g || d < 1 || d > 0xFFFFFFFFll || !(variance >= 0.f) || !aligned16(g)) return HOP_ERR_INVALID_ARG;
+    HopGradJob gj;
+    std::memset(&gj, 0, sizeof(gj));
+    gj.g = g;
+    hoprng::synth_keys(seed, worker, iter, &gj.k0, &gj.k1, &gj.k2);
+    gj.scale = hoprng::synth_scale(variance);
+    return run_one_grad(gj, HOP_GRAD_SYNTH, 0, d, 0.f, stream);
+}
+
+int hop_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || (bytes & 15u) || !aligned16(dst) || !aligned16(src)) return HOP_ERR_INVALID_ARG;
+    int rc = hopk_copy(dst, src, bytes, stream);
+    if (rc) return hip_fail(nullptr, (hipError_t)rc, "copy launch");
+    return HOP_OK;
+}
+
+int hop_download(void* host_dst, const void* dev_src, size_t bytes, void* stream) {
+    if (!host_dst || !dev_src) return HOP_ERR_INVALID_ARG;
+    if (bytes == 0) return HOP_OK;
+    HOP_HIP(nullptr, hipMemcpyAsync(host_dst, dev_src, bytes, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HOP_HIP(nullptr, hipStreamSynchronize((hipStream_t)stream));
+    return HOP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,126 @@
+// Internal declarations shared by the host side (hop_api.cpp, hop_sim.cpp) and the
+// kernels (hop_kernels.hip).  Nothing here is part of the public ABI.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "hop.h"
+
+// ---- device-side job descriptors (plain data, uploaded once per schedule) ----------
+struct alignas(16) HopMixJob {
+    float* out;
+    const float* g;            // null: no gradient term
+    float eta;
+    int32_t A;
+    int32_t pad0, pad1;
+    const float* src[HOP_MAX_A];
+    float w[HOP_MAX_A];
+};
+
+struct alignas(16) HopGradJob {
+    // dense: X row-major rows x d; csr: rowptr/col/val
+    const float* X;
+    const int64_t* rowptr;
+    const int32_t* col;
+    const float* val;
+    const float* y;
+    const float* w;            // x_{k,i}: the version the gradient is taken at
+    const int32_t* rows;       // B sample ids
+    float* g;                  // dense gradient buffer of the worker (dense / synth modes)
+    float* coef;               // B hinge coefficients of this record
+    float* partial;            // dense: B x nseg partial dot products
+    float* out;                // csr: the vector the sparse part is scattered into
+    uint32_t k0, k1, k2;       // synth: hash keys of (seed, worker, iteration)
+    float scale;               // synth: fp32 factor
+};
+
+// ---- kernel launchers (hop_kernels.hip); all return a hipError_t as int ------------
+int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream);
+int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream);
+int hopk_dense_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, void* stream);
+int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream);
+int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, void* stream);
+int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float eta, void* stream);
+int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream);
+int hopk_copy(void* dst, const void* src, size_t bytes, void* stream);
+int hopk_dense_nseg(int64_t d);                 // column segments per row in the margin pass
+
+// ---- host-side random numbers (hop_sim.cpp) ---------------------------------------
+namespace hoprng {
+enum : uint64_t { STREAM_DELAY = 1, STREAM_BATCH = 2, STREAM_SYNTHGRAD = 6 };
+uint64_t mix(uint64_t seed, uint64_t stream, uint64_t a, uint64_t b, uint64_t c);
+void synth_keys(uint64_t seed, int worker, int iter, uint32_t* k0, uint32_t* k1, uint32_t* k2);
+float synth_scale(float variance);
+}  // namespace hoprng
+
+// ---- schedule ----------------------------------------------------------------------
+struct hop_schedule {
+    int N = 0, D = 0, K = 0, batch = 0, stalled = 0, n_jumps = 0, n_waves = 0;
+    std::vector<int32_t> kind, worker, iter, wave, out_slot, src_begin, src_worker, src_tag, src_slot;
+    std::vector<uint64_t> time;
+    std::vector<float> src_weight;
+    std::vector<int32_t> batch_rows, final_iter, wave_begin, wave_order;
+    std::vector<uint64_t> finish_time;
+
+    // device side, built lazily by hop_step for the context's current gradient mode
+    const hop_ctx* owner = nullptr;
+    int built_mode = -1;
+    uint64_t built_epoch = 0;
+    HopMixJob* mix_dev = nullptr;       // n_records, in wave order
+    HopGradJob* grad_dev = nullptr;     // STEP records only, in wave order
+    int32_t* rows_dev = nullptr;        // n_records x batch
+    float* coef_dev = nullptr;          // n_records x batch
+    std::vector<int32_t> grad_begin;    // n_waves + 1 offsets into grad_dev
+    std::vector<double> wave_mix_bytes; // algorithmic bytes of each wave's mix launch
+    std::vector<double> wave_grad_bytes;
+};
+
+// ---- context -----------------------------------------------------------------------
+struct HopData {
+    int64_t rows = 0;
+    const float* X = nullptr;
+    const int64_t* rowptr = nullptr;
+    const int32_t* col = nullptr;
+    const float* val = nullptr;
+    const float* y = nullptr;
+};
+
+struct HopProfile {
+    std::vector<void*> ev;              // pairs of hipEvent_t, recycled
+    std::vector<int> pending_kernel;    // kernel id of each recorded pair
+    std::vector<double> pending_bytes;
+    double ms[HOP_KERNEL_COUNT] = {0, 0, 0};
+    int64_t launches[HOP_KERNEL_COUNT] = {0, 0, 0};
+    double bytes[HOP_KERNEL_COUNT] = {0, 0, 0};
+};
+
+struct hop_ctx {
+    int N = 0, s = 0, b = 0, D = 0, max_ig = 0;
+    int64_t d = 0, stride = 0;
+    hop_opts opts{};
+    std::vector<std::vector<int>> in_nbrs, out_nbrs;
+    std::vector<float> W;               // N x N, W[j*N+i]
+    // device
+    bool has_device = false;
+    char* arena = nullptr;
+    size_t arena_bytes = 0;
+    void* stream = nullptr;
+    float* ring = nullptr;              // N x D x stride
+    float* gbuf = nullptr;              // N x stride
+    float* partial = nullptr;           // N x batch x nseg
+    std::vector<HopData> data;
+    int grad_mode = HOP_GRAD_ZERO;
+    float synth_variance = 0.f;
+    const float* external = nullptr;
+    uint64_t epoch = 0;                 // bumped whenever job descriptors would change
+    std::vector<int32_t> version;       // newest iteration held per worker
+    const hop_schedule* running = nullptr;
+    int next_wave = 0;
+    bool profiling = false;
+    HopProfile prof;
+    std::string last_error;
+};
+
+int hop_run_protocol(const hop_ctx* ctx, const hop_delay_model* dm, int K, hop_schedule* out);

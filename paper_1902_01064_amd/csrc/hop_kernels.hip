@@ -1,0 +1,515 @@
+// HIP kernels of the Hop hot path for gfx950 (CDNA4, 64-wide wavefronts, 256 CUs in 8 XCDs).
+//
+// Every kernel here is bound by HBM bandwidth (about half a flop per byte), so none uses MFMA:
+// the work is coalesced 128-bit streaming, wavefront reductions and LDS staging of small tables.
+#include <hip/hip_runtime.h>
+
+#include "hop_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kXcd = 8;                 // workgroups are dealt round-robin to the 8 XCDs
+
+__device__ __forceinline__ float4 ld4(const float* p, int64_t i4) {
+    return reinterpret_cast<const float4*>(p)[i4];
+}
+__device__ __forceinline__ void st4(float* p, int64_t i4, float4 v) {
+    reinterpret_cast<float4*>(p)[i4] = v;
+}
+typedef float vf4 __attribute__((ext_vector_type(4)));
+// streaming (non-temporal) 128-bit accesses for data touched once
+__device__ __forceinline__ float4 ld4_stream(const float* p, int64_t i4) {
+    vf4 v = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(p) + i4);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st4_stream(float* p, int64_t i4, float4 v) {
+    vf4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<vf4*>(p) + i4);
+}
+
+// blockIdx -> (job, chunk) so that the 8 workgroups dealt to the 8 XCDs at the same moment work on
+// 8 different column chunks, and one XCD sees the same chunk for all jobs of a wave back to back:
+// a source vector read by several jobs (a worker and its neighbours all average it) is then
+// fetched from HBM once per XCD-local L2 instead of once per job.
+__device__ __forceinline__ bool map_block(int n_jobs, int64_t n_chunks, int* job, int64_t* chunk) {
+    int64_t b = blockIdx.x;
+    int xcd = (int)(b % kXcd);
+    int64_t local = b / kXcd;
+    *job = (int)(local % n_jobs);
+    *chunk = (local / n_jobs) * kXcd + xcd;
+    return *chunk < n_chunks;
+}
+
+inline int64_t grid_for(int n_jobs, int64_t n_chunks) {
+    int64_t padded = (n_chunks + kXcd - 1) / kXcd * kXcd;
+    return padded * n_jobs;
+}
+
+// ------------------------------------------------------------------------ Reduce + Apply ----
+// out[c] = sum_a w_a src_a[c] - eta g[c]   (Figure "Standard Decentralized Training", steps 2-3;
+// weights from Eq. 2 times the mixing matrix, already normalised on the host).
+constexpr int kMixVec = 4;              // float4 per thread per source
+constexpr int kMixChunk4 = kThreads * kMixVec;
+
+template <int A>
+__device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int64_t first4, int64_t n4) {
+    const float* g = job->g;
+    const float neg_eta = -job->eta;
+    float* out = job->out;
+    float4 acc[kMixVec];
+    int64_t idx[kMixVec];
+    bool ok[kMixVec];
+#pragma unroll
+    for (int u = 0; u < kMixVec; ++u) {
+        idx[u] = first4 + (int64_t)u * kThreads + threadIdx.x;
+        ok[u] = idx[u] < n4;
+    }
+    {
+        const float* s0 = job->src[0];
+        const float w0 = job->w[0];
+#pragma unroll
+        for (int u = 0; u < kMixVec; ++u) {
+            float4 v = ok[u] ? ld4(s0, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            acc[u] = make_float4(w0 * v.x, w0 * v.y, w0 * v.z, w0 * v.w);
+        }
+    }
+#pragma unroll
+    for (int a = 1; a < A; ++a) {
+        const float* sa = job->src[a];
+        const float wa = job->w[a];
+#pragma unroll
+        for (int u = 0; u < kMixVec; ++u) {
+            float4 v = ok[u] ? ld4(sa, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            acc[u].x = fmaf(wa, v.x, acc[u].x);
+            acc[u].y = fmaf(wa, v.y, acc[u].y);
+            acc[u].z = fmaf(wa, v.z, acc[u].z);
+            acc[u].w = fmaf(wa, v.w, acc[u].w);
+        }
+    }
+    if (g != nullptr) {
+#pragma unroll
+        for (int u = 0; u < kMixVec; ++u) {
+            float4 v = ok[u] ? ld4_stream(g, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            acc[u].x = fmaf(neg_eta, v.x, acc[u].x);
+            acc[u].y = fmaf(neg_eta, v.y, acc[u].y);
+            acc[u].z = fmaf(neg_eta, v.z, acc[u].z);
+            acc[u].w = fmaf(neg_eta, v.w, acc[u].w);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kMixVec; ++u)
+        if (ok[u]) st4_stream(out, idx[u], acc[u]);
+}
+
+__device__ __forceinline__ void mix_tile_any(const HopMixJob* __restrict__ job, int64_t first4, int64_t n4) {
+    const int A = job->A;
+    const float* g = job->g;
+    const float neg_eta = -job->eta;
+    for (int u = 0; u < kMixVec; ++u) {
+        int64_t i = first4 + (int64_t)u * kThreads + threadIdx.x;
+        if (i >= n4) continue;
+        float4 v = ld4(job->src[0], i);
+        float w = job->w[0];
+        float4 acc = make_float4(w * v.x, w * v.y, w * v.z, w * v.w);
+        for (int a = 1; a < A; ++a) {
+            v = ld4(job->src[a], i);
+            w = job->w[a];
+            acc.x = fmaf(w, v.x, acc.x);
+            acc.y = fmaf(w, v.y, acc.y);
+            acc.z = fmaf(w, v.z, acc.z);
+            acc.w = fmaf(w, v.w, acc.w);
+        }
+        if (g != nullptr) {
+            v = ld4_stream(g, i);
+            acc.x = fmaf(neg_eta, v.x, acc.x);
+            acc.y = fmaf(neg_eta, v.y, acc.y);
+            acc.z = fmaf(neg_eta, v.z, acc.z);
+            acc.w = fmaf(neg_eta, v.w, acc.w);
+        }
+        st4_stream(job->out, i, acc);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void mix_kernel(const HopMixJob* __restrict__ jobs, int n_jobs,
+                                                       int64_t d, int64_t n_chunks) {
+    int j;
+    int64_t chunk;
+    if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    const HopMixJob* job = jobs + j;
+    const int64_t n4 = d >> 2;
+    const int64_t first4 = chunk * kMixChunk4;
+    switch (job->A) {
+        case 1: mix_tile<1>(job, first4, n4); break;
+        case 2: mix_tile<2>(job, first4, n4); break;
+        case 3: mix_tile<3>(job, first4, n4); break;
+        case 4: mix_tile<4>(job, first4, n4); break;
+        case 5: mix_tile<5>(job, first4, n4); break;
+        case 6: mix_tile<6>(job, first4, n4); break;
+        case 7: mix_tile<7>(job, first4, n4); break;
+        case 8: mix_tile<8>(job, first4, n4); break;
+        case 9: mix_tile<9>(job, first4, n4); break;
+        case 10: mix_tile<10>(job, first4, n4); break;
+        case 11: mix_tile<11>(job, first4, n4); break;
+        case 12: mix_tile<12>(job, first4, n4); break;
+        default: mix_tile_any(job, first4, n4); break;
+    }
+    // the d mod 4 trailing columns, one thread each, by the workgroup of the last chunk
+    if (chunk == n_chunks - 1) {
+        int64_t c = (n4 << 2) + threadIdx.x;
+        if (threadIdx.x < 4 && c < d) {
+            float acc = job->w[0] * job->src[0][c];
+            for (int a = 1; a < job->A; ++a) acc = fmaf(job->w[a], job->src[a][c], acc);
+            if (job->g != nullptr) acc = fmaf(-job->eta, job->g[c], acc);
+            job->out[c] = acc;
+        }
+    }
+}
+
+// ------------------------------------------------------------------- synthetic gradient ----
+// g[c] = (sum of the 12 bytes of h32(c ^ k0), h32(c ^ k1), h32(c ^ k2) - 1530) * scale:
+// integer work and one correctly rounded multiply, so any implementation agrees bit for bit.
+__device__ __forceinline__ uint32_t h32(uint32_t x) {
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ uint32_t byte_sum(uint32_t x, uint32_t acc) {
+    return __builtin_amdgcn_sad_u8(x, 0u, acc);       // acc + sum of the four bytes of x
+}
+__device__ __forceinline__ float synth_one(uint32_t c, uint32_t k0, uint32_t k1, uint32_t k2, float scale) {
+    uint32_t s = byte_sum(h32(c ^ k0), 0u);
+    s = byte_sum(h32(c ^ k1), s);
+    s = byte_sum(h32(c ^ k2), s);
+    return (float)((int)s - 1530) * scale;
+}
+
+constexpr int kSynthVec = 2;
+constexpr int kSynthChunk4 = kThreads * kSynthVec;
+
+__global__ __launch_bounds__(kThreads) void synth_kernel(const HopGradJob* __restrict__ jobs, int n_jobs,
+                                                         int64_t d, int64_t n_chunks) {
+    int j;
+    int64_t chunk;
+    if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    const HopGradJob* job = jobs + j;
+    const uint32_t k0 = job->k0, k1 = job->k1, k2 = job->k2;
+    const float scale = job->scale;
+    float* g = job->g;
+    const int64_t n4 = d >> 2;
+#pragma unroll
+    for (int u = 0; u < kSynthVec; ++u) {
+        int64_t i = chunk * kSynthChunk4 + (int64_t)u * kThreads + threadIdx.x;
+        if (i < n4) {
+            uint32_t c = (uint32_t)(i << 2);
+            float4 v;
+            v.x = synth_one(c, k0, k1, k2, scale);
+            v.y = synth_one(c + 1, k0, k1, k2, scale);
+            v.z = synth_one(c + 2, k0, k1, k2, scale);
+            v.w = synth_one(c + 3, k0, k1, k2, scale);
+            st4(g, i, v);
+        }
+    }
+    if (chunk == n_chunks - 1) {
+        int64_t c = (n4 << 2) + threadIdx.x;
+        if (threadIdx.x < 4 && c < d) g[c] = synth_one((uint32_t)c, k0, k1, k2, scale);
+    }
+}
+
+// ------------------------------------------------------------------ wavefront reductions ----
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;                                          // lane 0 holds the sum
+}
+
+__device__ __forceinline__ float block_sum(float v, float* red) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) red[wv] = v;
+    __syncthreads();
+    float t = 0.f;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int k = 0; k < kThreads / 64; ++k) t += red[k];
+    }
+    return t;                                          // thread 0 holds the sum
+}
+
+// ------------------------------------------------------------- dense SVM: margins ("Compute") ----
+// One workgroup per (job, minibatch row, column segment): partial <x_r, w> over 16384 columns.
+constexpr int kSegVec = 16;
+constexpr int kSeg4 = kThreads * kSegVec;             // float4 per segment
+constexpr int64_t kSegCols = (int64_t)kSeg4 * 4;
+
+__global__ __launch_bounds__(kThreads) void dense_margin_kernel(const HopGradJob* __restrict__ jobs, int B,
+                                                                int64_t d, int nseg) {
+    __shared__ float red[kThreads / 64];
+    const int64_t b = blockIdx.x;
+    const int seg = (int)(b % nseg);
+    const int m = (int)((b / nseg) % B);
+    const HopGradJob* job = jobs + b / ((int64_t)nseg * B);
+    const float* x = job->X + (int64_t)job->rows[m] * d;
+    const float* w = job->w;
+    float acc = 0.f;
+    const int64_t lo = (int64_t)seg * kSegCols;
+    const int64_t hi = min(d, lo + kSegCols);
+    if ((d & 3) == 0) {
+        const int64_t lo4 = lo >> 2, hi4 = hi >> 2;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 4
+        for (int64_t i = lo4 + threadIdx.x; i < hi4; i += kThreads) {
+            float4 xv = ld4_stream(x, i);
+            float4 wv = ld4(w, i);
+            a0 = fmaf(xv.x, wv.x, a0);
+            a1 = fmaf(xv.y, wv.y, a1);
+            a2 = fmaf(xv.z, wv.z, a2);
+            a3 = fmaf(xv.w, wv.w, a3);
+        }
+        acc = (a0 + a1) + (a2 + a3);
+    } else {
+        for (int64_t c = lo + threadIdx.x; c < hi; c += kThreads) acc = fmaf(x[c], w[c], acc);
+    }
+    float tot = block_sum(acc, red);
+    if (threadIdx.x == 0) job->partial[(int64_t)m * nseg + seg] = tot;
+}
+
+// ----------------------------------------------------- dense SVM: g = lambda w - sum_m c_m x_m ----
+// One workgroup per (job, 1024-column chunk).  The hinge coefficients c_m = y_m / B if
+// y_m <x_m, w> < 1 else 0 are rebuilt by every workgroup from the partial dot products (B values,
+// cheap) and the active rows are compacted in LDS in minibatch order.
+constexpr int kMaxB = 1024;
+constexpr int kRowUnroll = 8;
+
+__global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* __restrict__ jobs, int n_jobs,
+                                                              int B, int64_t d, int nseg, float lambda,
+                                                              int64_t n_chunks) {
+    __shared__ float coefS[kMaxB + kRowUnroll];
+    __shared__ int rowS[kMaxB + kRowUnroll];
+    __shared__ float allC[kMaxB];
+    __shared__ int nactS;
+    int j;
+    int64_t chunk;
+    if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    const HopGradJob* job = jobs + j;
+    const float invB = 1.0f / (float)B;
+    for (int m = threadIdx.x; m < B; m += kThreads) {
+        float dot = 0.f;
+        for (int sg = 0; sg < nseg; ++sg) dot += job->partial[(int64_t)m * nseg + sg];
+        float y = job->y[job->rows[m]];
+        float c = (y * dot < 1.0f) ? y * invB : 0.f;
+        allC[m] = c;
+        if (chunk == 0) job->coef[m] = c;
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {                            // first wavefront compacts, keeping order
+        int count = 0;
+        for (int base = 0; base < B; base += 64) {
+            int m = base + threadIdx.x;
+            float c = m < B ? allC[m] : 0.f;
+            bool act = c != 0.f;
+            unsigned long long mask = __ballot(act);
+            int pos = count + __popcll(mask & ((1ull << threadIdx.x) - 1ull));
+            if (act) {
+                coefS[pos] = c;
+                rowS[pos] = job->rows[m];
+            }
+            count += __popcll(mask);
+        }
+        if (threadIdx.x < kRowUnroll) {                // pad to a multiple of the unroll with zeros
+            coefS[count + threadIdx.x] = 0.f;
+            rowS[count + threadIdx.x] = job->rows[0];
+        }
+        if (threadIdx.x == 0) nactS = count;
+    }
+    __syncthreads();
+    const int nact = nactS;
+    const float* X = job->X;
+    const float* w = job->w;
+    float* g = job->g;
+    if ((d & 3) == 0) {
+        const int64_t n4 = d >> 2;
+        const int64_t i = chunk * kThreads + threadIdx.x;
+        if (i < n4) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int n = 0; n < nact; n += kRowUnroll) {
+                float4 v[kRowUnroll];
+#pragma unroll
+                for (int u = 0; u < kRowUnroll; ++u) v[u] = ld4(X + (int64_t)rowS[n + u] * d, i);
+#pragma unroll
+                for (int u = 0; u < kRowUnroll; ++u) {
+                    const float c = coefS[n + u];
+                    acc.x = fmaf(c, v[u].x, acc.x);
+                    acc.y = fmaf(c, v[u].y, acc.y);
+                    acc.z = fmaf(c, v[u].z, acc.z);
+                    acc.w = fmaf(c, v[u].w, acc.w);
+                }
+            }
+            float4 wv = ld4(w, i);
+            st4(g, i, make_float4(fmaf(lambda, wv.x, -acc.x), fmaf(lambda, wv.y, -acc.y),
+                                  fmaf(lambda, wv.z, -acc.z), fmaf(lambda, wv.w, -acc.w)));
+        }
+    } else {
+        for (int q = 0; q < 4; ++q) {
+            const int64_t c = (chunk * kThreads + threadIdx.x) * 4 + q;
+            if (c < d) {
+                float acc = 0.f;
+                for (int n = 0; n < nact; ++n) acc = fmaf(coefS[n], X[(int64_t)rowS[n] * d + c], acc);
+                g[c] = fmaf(lambda, w[c], -acc);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------- CSR SVM: margins ----
+// One wavefront per (job, minibatch row): gather w[col], reduce across the 64 lanes.
+__global__ __launch_bounds__(kThreads) void csr_margin_kernel(const HopGradJob* __restrict__ jobs, int B,
+                                                              int rows_per_job_blocks) {
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const HopGradJob* job = jobs + blockIdx.x / rows_per_job_blocks;
+    const int m = (blockIdx.x % rows_per_job_blocks) * (kThreads / 64) + wv;
+    if (m >= B) return;
+    const int r = job->rows[m];
+    const int64_t lo = job->rowptr[r], hi = job->rowptr[r + 1];
+    const float* w = job->w;
+    float acc = 0.f;
+    for (int64_t p = lo + lane; p < hi; p += 64) acc = fmaf(job->val[p], w[job->col[p]], acc);
+    acc = wave_sum(acc);
+    if (lane == 0) {
+        float y = job->y[r];
+        job->coef[m] = (y * acc < 1.0f) ? y * (1.0f / (float)B) : 0.f;
+    }
+}
+
+// target[col] += factor * c_m * val for the active rows (the sparse part of -eta g, or of g).
+__global__ __launch_bounds__(kThreads) void csr_scatter_kernel(const HopGradJob* __restrict__ jobs, int B,
+                                                               int rows_per_job_blocks, float factor) {
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const HopGradJob* job = jobs + blockIdx.x / rows_per_job_blocks;
+    const int m = (blockIdx.x % rows_per_job_blocks) * (kThreads / 64) + wv;
+    if (m >= B) return;
+    const float c = job->coef[m];
+    if (c == 0.f) return;
+    const int r = job->rows[m];
+    const int64_t lo = job->rowptr[r], hi = job->rowptr[r + 1];
+    float* target = job->out;
+    const float f = factor * c;
+    for (int64_t p = lo + lane; p < hi; p += 64) unsafeAtomicAdd(target + job->col[p], f * job->val[p]);
+}
+
+// g = lambda w, the dense part of a CSR gradient when a dense g is wanted.
+__global__ __launch_bounds__(kThreads) void scale_kernel(const HopGradJob* __restrict__ jobs, int n_jobs,
+                                                         int64_t d, float lambda, int64_t n_chunks) {
+    int j;
+    int64_t chunk;
+    if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    const HopGradJob* job = jobs + j;
+    for (int q = 0; q < 4; ++q) {
+        int64_t c = (chunk * 4 + q) * kThreads + threadIdx.x;
+        if (c < d) job->out[c] = lambda * job->w[c];
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src,
+                                                        int64_t n16) {
+    int64_t i = (int64_t)blockIdx.x * (kThreads * 4) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < 4; ++u, i += kThreads)
+        if (i < n16) dst[i] = src[i];
+}
+
+inline int launch_status() { return (int)hipGetLastError(); }
+
+}  // namespace
+
+int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
+    if (n_jobs <= 0) return 0;
+    int64_t n4 = d >> 2;
+    int64_t n_chunks = (n4 + kMixChunk4 - 1) / kMixChunk4;
+    if (n_chunks < 1) n_chunks = 1;
+    int64_t grid = grid_for(n_jobs, n_chunks);
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(mix_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev, n_jobs,
+                       d, n_chunks);
+    return launch_status();
+}
+
+int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
+    if (n_jobs <= 0) return 0;
+    int64_t n4 = d >> 2;
+    int64_t n_chunks = (n4 + kSynthChunk4 - 1) / kSynthChunk4;
+    if (n_chunks < 1) n_chunks = 1;
+    int64_t grid = grid_for(n_jobs, n_chunks);
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(synth_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev,
+                       n_jobs, d, n_chunks);
+    return launch_status();
+}
+
+int hopk_dense_nseg(int64_t d) {
+    int64_t n = (d + kSegCols - 1) / kSegCols;
+    return (int)(n < 1 ? 1 : n);
+}
+
+int hopk_dense_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, void* stream) {
+    if (n_jobs <= 0 || B <= 0) return 0;
+    int nseg = hopk_dense_nseg(d);
+    int64_t grid = (int64_t)n_jobs * B * nseg;
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(dense_margin_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream,
+                       jobs_dev, B, d, nseg);
+    return launch_status();
+}
+
+int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream) {
+    if (n_jobs <= 0 || B <= 0) return 0;
+    if (B > kMaxB) return (int)hipErrorInvalidValue;
+    int nseg = hopk_dense_nseg(d);
+    int64_t n_chunks = (d + 4 * kThreads - 1) / (4 * kThreads);
+    int64_t grid = grid_for(n_jobs, n_chunks);
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(dense_grad_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev,
+                       n_jobs, B, d, nseg, lambda, n_chunks);
+    return launch_status();
+}
+
+int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, void* stream) {
+    if (n_jobs <= 0 || B <= 0) return 0;
+    int per = (B + kThreads / 64 - 1) / (kThreads / 64);
+    hipLaunchKernelGGL(csr_margin_kernel, dim3((unsigned)(n_jobs * per)), dim3(kThreads), 0, (hipStream_t)stream,
+                       jobs_dev, B, per);
+    return launch_status();
+}
+
+int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, void* stream) {
+    if (n_jobs <= 0 || B <= 0) return 0;
+    int per = (B + kThreads / 64 - 1) / (kThreads / 64);
+    hipLaunchKernelGGL(csr_scatter_kernel, dim3((unsigned)(n_jobs * per)), dim3(kThreads), 0, (hipStream_t)stream,
+                       jobs_dev, B, per, factor);
+    return launch_status();
+}
+
+int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream) {
+    if (n_jobs <= 0) return 0;
+    int64_t n_chunks = (d + 4 * kThreads - 1) / (4 * kThreads);
+    int64_t grid = grid_for(n_jobs, n_chunks);
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(scale_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev,
+                       n_jobs, d, lambda, n_chunks);
+    int rc = launch_status();
+    if (rc) return rc;
+    return hopk_csr_scatter(jobs_dev, n_jobs, B, -1.0f, stream);
+}
+
+int hopk_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    int64_t n16 = (int64_t)(bytes / 16);
+    if (n16 <= 0) return 0;
+    int64_t grid = (n16 + kThreads * 4 - 1) / (kThreads * 4);
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, (float4*)dst,
+                       (const float4*)src, n16);
+    return launch_status();
+}

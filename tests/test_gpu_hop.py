@@ -1,0 +1,249 @@
+"""GPU parity of the whole path (hop_init / hop_simulate / hop_step / hop_params through the C
+ABI) against the CPU oracle on the five synthetic workloads.
+
+Bars: schedules and accepted-slot indices bit-exact; fp32 parameters within a maximum relative
+error of 1e-5 for every single record (same inputs on both sides) and 1e-4 after the whole run
+(at most 100 iterations here).  The relative error is max_c |gpu - ref| / max(|ref_c|, rms(ref))
+(tests/parity.py says why); the figure with a floor of 1e-3 rms is printed beside it.  At a hinge margin within fp32 rounding of 1 either branch is a valid
+subgradient: the oracle then follows the branch the kernel took, and the test checks that the
+margin really was that close.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import arith, protocol, rng, waves
+from paper_1902_01064_amd import hop, inputs
+from parity import rel_err, strict_rel_err
+from paper_1902_01064_amd.session import Session, make_data
+
+pytestmark = pytest.mark.gpu
+
+STEP_TOL = 1e-5
+RUN_TOL = 1e-4
+
+
+
+def oracle_schedule(c, K):
+    h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], K, max_ig=c["max_ig"], skip_on=c["skip_on"],
+                     max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
+                     delay_kind=c["delay_kind"], mult=c["mult"], check=False)
+    recs = h.run()
+    return h, recs
+
+
+def assert_schedule_equal(sched, h, recs):
+    assert sched.n_records == len(recs) and sched.depth == h.D and not sched.stalled
+    assert list(sched.kind) == [r.kind for r in recs]
+    assert list(sched.worker) == [r.worker for r in recs]
+    assert list(sched.iter) == [r.k for r in recs]
+    assert list(sched.out_slot) == [r.out_slot for r in recs]
+    assert list(sched.src_worker) == [j for r in recs for j in r.src_worker]
+    assert list(sched.src_tag) == [t for r in recs for t in r.src_tag]
+    assert list(sched.src_slot) == [t for r in recs for t in r.src_slot]
+    w_ref = np.concatenate([r.w32 for r in recs])
+    assert np.array_equal(sched.src_weight.view(np.uint32), w_ref.view(np.uint32))
+    assert waves.check_waves(recs, list(sched.wave), h.N, h.D)
+
+
+class FollowKernelAtTies:
+    """Oracle gradient that takes the kernel's side where a margin is within rounding of the hinge
+    kink, and fails the test where the two disagree on anything else."""
+
+    def __init__(self, base, gpu_active, scale_of):
+        self.base, self.gpu_active, self.scale_of = base, gpu_active, scale_of
+        self.flips = 0
+
+    def __call__(self, i, k, w):
+        g = self.base(i, k, w)
+        rows, margins, act = self.base.log[(i, k)]
+        ga = self.gpu_active[(i, k)]
+        diff = act != ga
+        if diff.any():
+            scale = self.scale_of(i, rows[diff], w)
+            assert np.all(np.abs(1.0 - margins[diff]) <= 1e-5 * (1.0 + scale)), (i, k, margins[diff])
+            self.base.force[(i, k)] = ga
+            g = self.base(i, k, w)
+            del self.base.force[(i, k)]
+            self.flips += int(diff.sum())
+        return g
+
+
+def oracle_grad(c, data, cols=None):
+    """(gradient callable, function giving sum |x w| of some rows) for a config's model."""
+    if c["model"] == "dense":
+        X = [x.numpy() for x in data[0]]
+        y = [t.numpy() for t in data[1]]
+        base = arith.GradSvmDense(c["seed"], X, y, c["batch"], c["lam"])
+        return base, lambda i, rows, w: np.abs(X[i][rows].astype(np.float64) * w.astype(np.float64)).sum(1)
+    if c["model"] == "csr":
+        dn = [tuple(t.numpy() for t in dd) for dd in data]
+        base = arith.GradSvmCsr(c["seed"], dn, c["batch"], c["lam"])
+
+        def scale(i, rows, w):
+            rp, cn, vn, _ = dn[i]
+            return np.array([np.abs(vn[rp[r]:rp[r + 1]].astype(np.float64) * w[cn[rp[r]:rp[r + 1]]]).sum()
+                             for r in rows])
+        return base, scale
+    if c["model"] == "synth":
+        return arith.GradSynth(c["seed"], c["grad_var"], np.arange(c["d"]) if cols is None else cols), None
+    return arith.GradZero(), None
+
+
+def attach(sess, c, p0, data):
+    if c["model"] == "dense":
+        sess.set_dense(*data)
+    elif c["model"] == "csr":
+        sess.set_csr(data)
+    elif c["model"] == "synth":
+        hop.hop_set_grad_source(sess.ctx, hop.HOP_GRAD_SYNTH, c["grad_var"])
+    sess.set_params(p0)
+
+
+def run_parity(c, per_wave_check=True):
+    """Whole run on the GPU and in the oracle; returns worst per-record and end-of-run errors."""
+    print("parity", c["name"], "N=%d d=%d K=%d" % (c["N"], c["d"], c["K"]), flush=True)
+    p0, data = make_data(c)
+    h, recs = oracle_schedule(c, c["K"])
+    sess = Session(c)
+    try:
+        attach(sess, c, p0, data)
+        sched = sess.simulate()
+        assert_schedule_equal(sched, h, recs)
+        base, scale_of = oracle_grad(c, data)
+        has_hinge = c["model"] in ("dense", "csr")
+        worst_step = strict_step = 0.0
+        gpu_active = {}
+        # ---- every record on its own: oracle arithmetic on the GPU's own inputs of that wave ----
+        for w in range(sched.n_waves):
+            before = sess.ring_snapshot() if per_wave_check else None
+            sess.step(w, w + 1)
+            sess.sync()
+            members = [int(e) for e in sched.wave_order[sched.wave_begin[w]:sched.wave_begin[w + 1]]]
+            if has_hinge:
+                for e in members:
+                    if recs[e].kind == protocol.STEP:
+                        gpu_active[(recs[e].worker, recs[e].k)] = sess.coef(e) != 0
+            if not per_wave_check:
+                continue
+            after = sess.ring_snapshot()
+            for e in members:
+                r = recs[e]
+                grad = FollowKernelAtTies(base, gpu_active, scale_of) if has_hinge else base
+                vecs = [before[j, sl] for j, sl in zip(r.src_worker, r.src_slot)]
+                g = grad(r.worker, r.k, vecs[0]) if r.kind == protocol.STEP else None
+                ref = arith.reduce_apply(vecs, r.w32, g, c["lr"])
+                worst_step = max(worst_step, rel_err(after[r.worker, r.out_slot], ref))
+                strict_step = max(strict_step, strict_rel_err(after[r.worker, r.out_slot], ref))
+        assert worst_step <= STEP_TOL, worst_step
+        # ---- the run as a whole: the oracle from p0 in sequence order ----
+        rings = arith.init_rings(p0.numpy(), c["N"], h.D)
+        grad = FollowKernelAtTies(base, gpu_active, scale_of) if has_hinge else base
+        ver = arith.execute(recs, rings, grad, c["lr"])
+        want = arith.final_params(rings, ver)
+        got, its = sess.params()
+        assert its == ver == [c["K"]] * c["N"]
+        gotn = [got[i].cpu().numpy() for i in range(c["N"])]
+        worst_run = max(rel_err(gotn[i], want[i]) for i in range(c["N"]))
+        strict_run = max(strict_rel_err(gotn[i], want[i]) for i in range(c["N"]))
+        print("  records %d waves %d jumps %d  per-record err %.2e (floor 1e-3 rms: %.2e)  end-of-run err "
+              "%.2e (floor 1e-3 rms: %.2e)  ties followed %d"
+              % (len(recs), sched.n_waves, sched.n_jumps, worst_step, strict_step, worst_run, strict_run,
+                 grad.flips if has_hinge else 0), flush=True)
+        assert worst_run <= RUN_TOL, worst_run
+        return worst_step, worst_run
+    finally:
+        sess.close()
+
+
+def test_cfg1_ring4_dense_full_size():
+    run_parity(inputs.config(1))
+
+
+def test_cfg2_ring16_dense_reduced():
+    run_parity(inputs.config(2, d=8192 + 4, rows=512, K=40))
+
+
+def test_cfg3_torus16_csr_reduced():
+    run_parity(inputs.config(3, d=1 << 14, rows=2048, K=40))
+
+
+def test_cfg4_chords32_mix_reduced():
+    run_parity(inputs.config(4, d=(1 << 15) + 3, K=100), per_wave_check=False)
+    run_parity(inputs.config(4, d=4096, K=30))
+
+
+def test_cfg5_torus64_csr_reduced():
+    run_parity(inputs.config(5, d=1 << 13, rows=1024, K=24))
+
+
+@pytest.mark.parametrize("s,b,skip,ig", [(0, 0, False, 0), (0, 1, True, 3), (2, 1, True, 4), (3, 0, False, 0)])
+def test_other_modes_with_external_and_zero_gradient(s, b, skip, ig):
+    """Exact-tag mode (ring depth max_ig + 2), backup workers, hybrid, jumps; caller-owned and zero
+    gradients."""
+    nb = inputs.torus(3, 3)
+    mult = [1.0] * 9
+    mult[4] = 3.0
+    c = dict(name="modes s=%d b=%d" % (s, b), in_nbrs=nb, W=inputs.metropolis_weights(nb), N=9, d=2048, s=s, b=b,
+             max_ig=ig, skip_on=skip, max_skip=10, trigger=1, lr=0.05, lam=0.0, batch=0, rows=0, seed=77,
+             delay_kind=hop.HOP_DELAY_EXP1, mult=mult, K=30, model="none")
+    h, recs = oracle_schedule(c, c["K"])
+    p0 = torch.randn(9, 2048, generator=torch.Generator().manual_seed(3))
+    gext = torch.randn(9, 2048, generator=torch.Generator().manual_seed(4)) * 0.1
+    for mode in ("external", "zero"):
+        sess = Session(c)
+        try:
+            gdev = gext.to(sess.dev)
+            if mode == "external":
+                hop.hop_set_grad_source(sess.ctx, hop.HOP_GRAD_EXTERNAL, 0.0, gdev.data_ptr())
+            sess.set_params(p0)
+            sched = sess.simulate()
+            assert_schedule_equal(sched, h, recs)
+            sess.step(0, sched.n_waves // 2)
+            sess.step(sched.n_waves // 2, -1)                 # resumable in the middle
+            sess.sync()
+            rings = arith.init_rings(p0.numpy(), 9, h.D)
+            gn = gext.numpy()
+            grad = (lambda i, k, w: gn[i].astype(np.float64)) if mode == "external" else arith.GradZero()
+            ver = arith.execute(recs, rings, grad, c["lr"])
+            want = arith.final_params(rings, ver)
+            got, its = sess.params()
+            assert its == ver
+            assert max(rel_err(got[i].cpu().numpy(), want[i]) for i in range(9)) <= RUN_TOL
+            with pytest.raises(hop.HopError) as e:
+                sess.step(5, 6)                               # waves out of sequence
+            assert e.value.code == hop.HOP_ERR_STATE
+        finally:
+            sess.close()
+
+
+def test_cfg4_full_size_sampled_columns():
+    """Workload of the benchmark at its real size (N = 32, d = 25 000 000, 100 iterations), in the
+    launch configuration the benchmark times; the oracle follows a seeded sample of 2^14 columns
+    (the update is separable by column and the synthetic gradient can be regenerated per element)."""
+    c = inputs.config(4)
+    print("parity", c["name"], "full size, sampled columns", flush=True)
+    h, recs = oracle_schedule(c, c["K"])
+    cols = np.unique(np.concatenate([
+        np.random.default_rng(1).integers(0, c["d"], size=1 << 14),
+        np.arange(0, 64), np.arange(c["d"] - 64, c["d"])]))
+    p0 = inputs.initial_params(c["seed"], c["d"], 0.01)
+    sess = Session(c)
+    try:
+        hop.hop_set_grad_source(sess.ctx, hop.HOP_GRAD_SYNTH, c["grad_var"])
+        sess.set_params(p0)
+        sched = sess.simulate()
+        assert_schedule_equal(sched, h, recs)
+        sess.step()
+        sess.sync()
+        got, its = sess.params()
+        rings = arith.init_rings(p0.numpy()[cols], c["N"], h.D)
+        ver = arith.execute(recs, rings, arith.GradSynth(c["seed"], c["grad_var"], cols), c["lr"])
+        want = arith.final_params(rings, ver)
+        assert its == ver
+        idx = torch.from_numpy(cols).to(sess.dev)
+        worst = max(rel_err(got[i][idx].cpu().numpy(), want[i]) for i in range(c["N"]))
+        print("  end-of-run err on %d sampled columns: %.2e" % (len(cols), worst), flush=True)
+        assert worst <= RUN_TOL
+    finally:
+        sess.close()
