@@ -79,7 +79,20 @@ def main():
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--d", type=int, default=0, help="override the parameter count (not a valid bench line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="only run the plain copy kernel on BYTES (for scaling rocprofv3 traffic counters)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        from paper_1902_01064_amd import hop
+        n = args.copy_calibration // 4
+        a = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(5):
+            hop.hop_copy(b.data_ptr(), a.data_ptr(), n * 4, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": n * 4, "launches": 5}))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
