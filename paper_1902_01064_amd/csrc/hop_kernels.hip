@@ -4,6 +4,8 @@
 // the work is coalesced 128-bit streaming, wavefront reductions and LDS staging of small tables.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "hop_internal.h"
 
 namespace {
@@ -49,28 +51,42 @@ inline int64_t grid_for(int n_jobs, int64_t n_chunks) {
 // ------------------------------------------------------------------------ Reduce + Apply ----
 // out[c] = sum_a w_a src_a[c] - eta g[c]   (Figure "Standard Decentralized Training", steps 2-3;
 // weights from Eq. 2 times the mixing matrix, already normalised on the host).
-constexpr int kMixVec = 4;              // float4 per thread per source
-constexpr int kMixChunk4 = kThreads * kMixVec;
+//
+// Template knobs: VEC float4 per thread per source; NT 0 = ordinary accesses, 1 = g and the result
+// non-temporal (each touched once), 2 = sources too; MAP 0 = job-major blocks, 1 = the XCD-aware map
+// above, 2 = chunk-major without regard to XCDs; T threads per workgroup.
+template <int NT>
+__device__ __forceinline__ float4 ld_src(const float* p, int64_t i) {
+    return NT >= 2 ? ld4_stream(p, i) : ld4(p, i);
+}
+template <int NT>
+__device__ __forceinline__ float4 ld_once(const float* p, int64_t i) {
+    return NT >= 1 ? ld4_stream(p, i) : ld4(p, i);
+}
+template <int NT>
+__device__ __forceinline__ void st_once(float* p, int64_t i, float4 v) {
+    if (NT >= 1) st4_stream(p, i, v); else st4(p, i, v);
+}
 
-template <int A>
+template <int A, int VEC, int NT, int T>
 __device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int64_t first4, int64_t n4) {
     const float* g = job->g;
     const float neg_eta = -job->eta;
     float* out = job->out;
-    float4 acc[kMixVec];
-    int64_t idx[kMixVec];
-    bool ok[kMixVec];
+    float4 acc[VEC];
+    int64_t idx[VEC];
+    bool ok[VEC];
 #pragma unroll
-    for (int u = 0; u < kMixVec; ++u) {
-        idx[u] = first4 + (int64_t)u * kThreads + threadIdx.x;
+    for (int u = 0; u < VEC; ++u) {
+        idx[u] = first4 + (int64_t)u * T + threadIdx.x;
         ok[u] = idx[u] < n4;
     }
     {
         const float* s0 = job->src[0];
         const float w0 = job->w[0];
 #pragma unroll
-        for (int u = 0; u < kMixVec; ++u) {
-            float4 v = ok[u] ? ld4(s0, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < VEC; ++u) {
+            float4 v = ok[u] ? ld_src<NT>(s0, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
             acc[u] = make_float4(w0 * v.x, w0 * v.y, w0 * v.z, w0 * v.w);
         }
     }
@@ -79,8 +95,8 @@ __device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int6
         const float* sa = job->src[a];
         const float wa = job->w[a];
 #pragma unroll
-        for (int u = 0; u < kMixVec; ++u) {
-            float4 v = ok[u] ? ld4(sa, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < VEC; ++u) {
+            float4 v = ok[u] ? ld_src<NT>(sa, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
             acc[u].x = fmaf(wa, v.x, acc[u].x);
             acc[u].y = fmaf(wa, v.y, acc[u].y);
             acc[u].z = fmaf(wa, v.z, acc[u].z);
@@ -89,8 +105,8 @@ __device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int6
     }
     if (g != nullptr) {
 #pragma unroll
-        for (int u = 0; u < kMixVec; ++u) {
-            float4 v = ok[u] ? ld4_stream(g, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < VEC; ++u) {
+            float4 v = ok[u] ? ld_once<NT>(g, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
             acc[u].x = fmaf(neg_eta, v.x, acc[u].x);
             acc[u].y = fmaf(neg_eta, v.y, acc[u].y);
             acc[u].z = fmaf(neg_eta, v.z, acc[u].z);
@@ -98,22 +114,24 @@ __device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int6
         }
     }
 #pragma unroll
-    for (int u = 0; u < kMixVec; ++u)
-        if (ok[u]) st4_stream(out, idx[u], acc[u]);
+    for (int u = 0; u < VEC; ++u)
+        if (ok[u]) st_once<NT>(out, idx[u], acc[u]);
 }
 
+// more than 12 sources: a loop over the sources instead of an unrolled chain
+template <int VEC, int NT, int T>
 __device__ __forceinline__ void mix_tile_any(const HopMixJob* __restrict__ job, int64_t first4, int64_t n4) {
     const int A = job->A;
     const float* g = job->g;
     const float neg_eta = -job->eta;
-    for (int u = 0; u < kMixVec; ++u) {
-        int64_t i = first4 + (int64_t)u * kThreads + threadIdx.x;
+    for (int u = 0; u < VEC; ++u) {
+        int64_t i = first4 + (int64_t)u * T + threadIdx.x;
         if (i >= n4) continue;
-        float4 v = ld4(job->src[0], i);
+        float4 v = ld_src<NT>(job->src[0], i);
         float w = job->w[0];
         float4 acc = make_float4(w * v.x, w * v.y, w * v.z, w * v.w);
         for (int a = 1; a < A; ++a) {
-            v = ld4(job->src[a], i);
+            v = ld_src<NT>(job->src[a], i);
             w = job->w[a];
             acc.x = fmaf(w, v.x, acc.x);
             acc.y = fmaf(w, v.y, acc.y);
@@ -121,38 +139,47 @@ __device__ __forceinline__ void mix_tile_any(const HopMixJob* __restrict__ job, 
             acc.w = fmaf(w, v.w, acc.w);
         }
         if (g != nullptr) {
-            v = ld4_stream(g, i);
+            v = ld_once<NT>(g, i);
             acc.x = fmaf(neg_eta, v.x, acc.x);
             acc.y = fmaf(neg_eta, v.y, acc.y);
             acc.z = fmaf(neg_eta, v.z, acc.z);
             acc.w = fmaf(neg_eta, v.w, acc.w);
         }
-        st4_stream(job->out, i, acc);
+        st_once<NT>(job->out, i, acc);
     }
 }
 
-__global__ __launch_bounds__(kThreads) void mix_kernel(const HopMixJob* __restrict__ jobs, int n_jobs,
-                                                       int64_t d, int64_t n_chunks) {
+template <int VEC, int NT, int MAP, int T>
+__global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jobs, int n_jobs, int64_t d,
+                                                int64_t n_chunks) {
     int j;
     int64_t chunk;
-    if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    if (MAP == 1) {
+        if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    } else if (MAP == 0) {
+        j = (int)(blockIdx.x / n_chunks);
+        chunk = blockIdx.x % n_chunks;
+    } else {
+        j = (int)(blockIdx.x % n_jobs);
+        chunk = blockIdx.x / n_jobs;
+    }
     const HopMixJob* job = jobs + j;
     const int64_t n4 = d >> 2;
-    const int64_t first4 = chunk * kMixChunk4;
+    const int64_t first4 = chunk * (int64_t)(T * VEC);
     switch (job->A) {
-        case 1: mix_tile<1>(job, first4, n4); break;
-        case 2: mix_tile<2>(job, first4, n4); break;
-        case 3: mix_tile<3>(job, first4, n4); break;
-        case 4: mix_tile<4>(job, first4, n4); break;
-        case 5: mix_tile<5>(job, first4, n4); break;
-        case 6: mix_tile<6>(job, first4, n4); break;
-        case 7: mix_tile<7>(job, first4, n4); break;
-        case 8: mix_tile<8>(job, first4, n4); break;
-        case 9: mix_tile<9>(job, first4, n4); break;
-        case 10: mix_tile<10>(job, first4, n4); break;
-        case 11: mix_tile<11>(job, first4, n4); break;
-        case 12: mix_tile<12>(job, first4, n4); break;
-        default: mix_tile_any(job, first4, n4); break;
+        case 1: mix_tile<1, VEC, NT, T>(job, first4, n4); break;
+        case 2: mix_tile<2, VEC, NT, T>(job, first4, n4); break;
+        case 3: mix_tile<3, VEC, NT, T>(job, first4, n4); break;
+        case 4: mix_tile<4, VEC, NT, T>(job, first4, n4); break;
+        case 5: mix_tile<5, VEC, NT, T>(job, first4, n4); break;
+        case 6: mix_tile<6, VEC, NT, T>(job, first4, n4); break;
+        case 7: mix_tile<7, VEC, NT, T>(job, first4, n4); break;
+        case 8: mix_tile<8, VEC, NT, T>(job, first4, n4); break;
+        case 9: mix_tile<9, VEC, NT, T>(job, first4, n4); break;
+        case 10: mix_tile<10, VEC, NT, T>(job, first4, n4); break;
+        case 11: mix_tile<11, VEC, NT, T>(job, first4, n4); break;
+        case 12: mix_tile<12, VEC, NT, T>(job, first4, n4); break;
+        default: mix_tile_any<VEC, NT, T>(job, first4, n4); break;
     }
     // the d mod 4 trailing columns, one thread each, by the workgroup of the last chunk
     if (chunk == n_chunks - 1) {
@@ -164,6 +191,19 @@ __global__ __launch_bounds__(kThreads) void mix_kernel(const HopMixJob* __restri
             job->out[c] = acc;
         }
     }
+}
+
+template <int VEC, int NT, int MAP, int T>
+int launch_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
+    int64_t n4 = d >> 2;
+    int64_t per = (int64_t)T * VEC;
+    int64_t n_chunks = (n4 + per - 1) / per;
+    if (n_chunks < 1) n_chunks = 1;
+    int64_t grid = MAP == 1 ? grid_for(n_jobs, n_chunks) : n_chunks * n_jobs;
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((mix_kernel<VEC, NT, MAP, T>), dim3((unsigned)grid), dim3(T), 0, (hipStream_t)stream,
+                       jobs_dev, n_jobs, d, n_chunks);
+    return (int)hipGetLastError();
 }
 
 // ------------------------------------------------------------------- synthetic gradient ----
@@ -427,14 +467,28 @@ inline int launch_status() { return (int)hipGetLastError(); }
 
 int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
     if (n_jobs <= 0) return 0;
-    int64_t n4 = d >> 2;
-    int64_t n_chunks = (n4 + kMixChunk4 - 1) / kMixChunk4;
-    if (n_chunks < 1) n_chunks = 1;
-    int64_t grid = grid_for(n_jobs, n_chunks);
-    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(mix_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev, n_jobs,
-                       d, n_chunks);
-    return launch_status();
+#ifdef HOP_TUNE
+    // tuning builds only: pick a variant by HOP_MIX_VARIANT (never compiled into the product)
+    static const int variant = getenv("HOP_MIX_VARIANT") ? atoi(getenv("HOP_MIX_VARIANT")) : 0;
+    switch (variant) {
+        case 1: return launch_mix<2, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
+        case 2: return launch_mix<8, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
+        case 3: return launch_mix<1, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
+        case 4: return launch_mix<4, 0, 1, 256>(jobs_dev, n_jobs, d, stream);
+        case 5: return launch_mix<4, 2, 1, 256>(jobs_dev, n_jobs, d, stream);
+        case 6: return launch_mix<4, 1, 0, 256>(jobs_dev, n_jobs, d, stream);
+        case 7: return launch_mix<4, 1, 2, 256>(jobs_dev, n_jobs, d, stream);
+        case 8: return launch_mix<2, 1, 1, 512>(jobs_dev, n_jobs, d, stream);
+        case 9: return launch_mix<4, 1, 1, 512>(jobs_dev, n_jobs, d, stream);
+        case 10: return launch_mix<1, 1, 1, 1024>(jobs_dev, n_jobs, d, stream);
+        case 11: return launch_mix<2, 0, 1, 256>(jobs_dev, n_jobs, d, stream);
+        case 12: return launch_mix<2, 1, 1, 128>(jobs_dev, n_jobs, d, stream);
+        case 13: return launch_mix<4, 1, 1, 128>(jobs_dev, n_jobs, d, stream);
+        case 14: return launch_mix<1, 1, 1, 512>(jobs_dev, n_jobs, d, stream);
+        default: break;
+    }
+#endif
+    return launch_mix<4, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
 }
 
 int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
