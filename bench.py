@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--d", type=int, default=0, help="override the parameter count (not a valid bench line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="time HIP-graph replays of the pass (kernel figures then come from one extra, "
+                         "untimed kernel-by-kernel pass)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="only run the plain copy kernel on BYTES (for scaling rocprofv3 traffic counters)")
     args = ap.parse_args()
@@ -121,16 +124,23 @@ def main():
     n_jump = int((sched.kind == hop.HOP_JUMP).sum())
     A = (sched.src_begin[1:] - sched.src_begin[:-1])
 
+    if args.graph:
+        hop.hop_use_graph(sess.ctx, 1)
     for _ in range(args.warmup):
         sess.step()
     sess.sync()
-    hop.hop_profile(sess.ctx, 1)
+    if not args.graph:
+        hop.hop_profile(sess.ctx, 1)
     sess.sync()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         sess.step()
     sess.sync()
     t1 = time.perf_counter()
+    if args.graph:
+        hop.hop_profile(sess.ctx, 1)
+        sess.step()
+        sess.sync()
     mix_ms, mix_n, mix_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_MIX)
     grad_ms, grad_n, grad_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_GRAD)
     syn_ms, syn_n, syn_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_SYNTH)
@@ -157,6 +167,7 @@ def main():
             "step_records": n_step, "jump_records": n_jump, "waves": int(sched.n_waves),
             "mean_A": float(A.mean()), "max_A": int(A.max()),
             "step_definition": "one pass of hop_step over the whole schedule",
+            "launch": "hip graph replay" if args.graph else "kernel by kernel",
         },
         "roofline": {
             "bound": "hbm", "kernel": "mix_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -207,6 +207,13 @@ int hop_schedule_free(hop_schedule* s);
  * wave 0 without resetting parameters (it then continues from whatever the rings hold). */
 int hop_step(hop_ctx* ctx, const hop_schedule* s, int32_t wave_begin, int32_t wave_end);
 
+/* With enable != 0, a hop_step call that covers the whole schedule (wave_begin 0, wave_end -1 or
+ * n_waves) and is not being profiled records its launches once into a HIP graph and replays that
+ * graph from then on: one launch call per pass instead of up to four per wave, which is what
+ * matters for schedules of many small waves (Exp(1) delays de-synchronise the workers).  Partial
+ * ranges and profiled passes always run kernel by kernel.  Off by default. */
+int hop_use_graph(hop_ctx* ctx, int enable);
+
 /* Newest parameter vector of a worker (device, d floats) and its iteration number. */
 int hop_params(hop_ctx* ctx, int32_t worker, const float** dev_ptr, int32_t* iter);
 /* Address of one ring slot (device, d floats). */

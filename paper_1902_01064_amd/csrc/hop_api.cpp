@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -25,7 +26,12 @@ int effective_max_ig(int s, const hop_opts* o) {
 
 // Every slot starts on a 256-byte boundary; the extra 256 bytes keep the slots of a power-of-two d
 // from all mapping to the same HBM channel phase.
-int64_t slot_stride(int64_t d) { return round_up(d, kAlignFloats) + kAlignFloats; }
+int64_t slot_stride(int64_t d) {
+#ifdef HOP_TUNE
+    if (const char* e = getenv("HOP_PAD_FLOATS")) return round_up(d, kAlignFloats) + atoll(e);
+#endif
+    return round_up(d, kAlignFloats) + kAlignFloats;
+}
 
 int64_t partial_floats(int64_t d, int batch) {
     return round_up((int64_t)std::max(batch, 1) * hopk_dense_nseg(d), kAlignFloats);
@@ -59,6 +65,8 @@ void free_device_side(hop_schedule* s) {
     s->rows_dev = nullptr;
     s->coef_dev = nullptr;
     s->built_mode = -1;
+    if (s->graph_exec) (void)hipGraphExecDestroy((hipGraphExec_t)s->graph_exec);
+    s->graph_exec = nullptr;
 }
 
 float* slot_ptr(const hop_ctx* c, int worker, int slot) {
@@ -336,6 +344,7 @@ int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64
 int hop_destroy(hop_ctx* c) {
     if (!c) return HOP_ERR_INVALID_ARG;
     for (void* e : c->prof.ev) (void)hipEventDestroy((hipEvent_t)e);
+    if (c->capture_stream) (void)hipStreamDestroy((hipStream_t)c->capture_stream);
     delete c;
     return HOP_OK;
 }
@@ -467,6 +476,74 @@ int hop_schedule_free(hop_schedule* s) {
     return HOP_OK;
 }
 
+// Enqueue the kernels of waves [wb, we) on `stream`.  `timed` brackets every kernel group with
+// profiling events (never while a stream is being captured into a graph).
+static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* stream, bool timed) {
+    const int B = s->batch;
+    const int mode = c->grad_mode;
+    for (int w = wb; w < we; ++w) {
+        const int jb = s->wave_begin[w], nj = s->wave_begin[w + 1] - jb;
+        const int gb = s->grad_begin[w], ng = s->grad_begin[w + 1] - gb;
+        const HopGradJob* gj = s->grad_dev ? s->grad_dev + gb : nullptr;
+        int rc;
+        if (ng > 0 && mode == HOP_GRAD_SYNTH) {
+            if (timed && (rc = prof_begin(c, HOP_KERNEL_SYNTH, s->wave_grad_bytes[w]))) return rc;
+            HOP_LAUNCH(c, hopk_synth(gj, ng, c->d, stream));
+            if (timed && (rc = prof_end(c))) return rc;
+        } else if (ng > 0 && mode == HOP_GRAD_SVM_DENSE) {
+            if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
+            HOP_LAUNCH(c, hopk_dense_margin(gj, ng, B, c->d, stream));
+            HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, stream));
+            if (timed && (rc = prof_end(c))) return rc;
+        } else if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
+            if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
+            HOP_LAUNCH(c, hopk_csr_margin(gj, ng, B, stream));
+            if (timed && (rc = prof_end(c))) return rc;
+        }
+        if (timed && (rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
+        HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, stream));
+        if (timed && (rc = prof_end(c))) return rc;
+        if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
+            if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, 0.0))) return rc;
+            HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, c->opts.lr, stream));
+            if (timed && (rc = prof_end(c))) return rc;
+        }
+    }
+    return HOP_OK;
+}
+
+// Record waves [0, n_waves) once into a HIP graph (captured on a stream of the library's own, default
+// priority; the caller's may be the null stream, which cannot be captured) and keep the executable.
+static int capture_graph(hop_ctx* c, hop_schedule* s) {
+    if (s->graph_exec) {
+        (void)hipGraphExecDestroy((hipGraphExec_t)s->graph_exec);
+        s->graph_exec = nullptr;
+    }
+    if (!c->capture_stream) {
+        hipStream_t st;
+        HOP_HIP(c, hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+        c->capture_stream = (void*)st;
+    }
+    hipStream_t cs = (hipStream_t)c->capture_stream;
+    HOP_HIP(c, hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
+    int rc = launch_waves(c, s, 0, s->n_waves, c->capture_stream, false);
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(cs, &graph);
+    if (rc != HOP_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+    }
+    if (e != hipSuccess) return hip_fail(c, e, "hipStreamEndCapture");
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) return hip_fail(c, e, "hipGraphInstantiate");
+    s->graph_exec = (void*)exec;
+    s->graph_epoch = c->epoch;
+    s->graph_mode = c->grad_mode;
+    return HOP_OK;
+}
+
 int hop_step(hop_ctx* c, const hop_schedule* sched, int32_t wave_begin, int32_t wave_end) {
     if (!c || !sched) return HOP_ERR_INVALID_ARG;
     if (!c->has_device) return HOP_ERR_NO_DEVICE;
@@ -480,41 +557,26 @@ int hop_step(hop_ctx* c, const hop_schedule* sched, int32_t wave_begin, int32_t 
         if (rc != HOP_OK) return rc;
     }
     c->running = s;
-    const int B = s->batch;
-    const int mode = c->grad_mode;
-    for (int w = wave_begin; w < wave_end; ++w) {
-        const int jb = s->wave_begin[w], nj = s->wave_begin[w + 1] - jb;
-        const int gb = s->grad_begin[w], ng = s->grad_begin[w + 1] - gb;
-        const HopGradJob* gj = s->grad_dev ? s->grad_dev + gb : nullptr;
-        int rc;
-        if (ng > 0 && mode == HOP_GRAD_SYNTH) {
-            if ((rc = prof_begin(c, HOP_KERNEL_SYNTH, s->wave_grad_bytes[w]))) return rc;
-            HOP_LAUNCH(c, hopk_synth(gj, ng, c->d, c->stream));
-            if ((rc = prof_end(c))) return rc;
-        } else if (ng > 0 && mode == HOP_GRAD_SVM_DENSE) {
-            if ((rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
-            HOP_LAUNCH(c, hopk_dense_margin(gj, ng, B, c->d, c->stream));
-            HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, c->stream));
-            if ((rc = prof_end(c))) return rc;
-        } else if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
-            if ((rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
-            HOP_LAUNCH(c, hopk_csr_margin(gj, ng, B, c->stream));
-            if ((rc = prof_end(c))) return rc;
-        }
-        if ((rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
-        HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, c->stream));
-        if ((rc = prof_end(c))) return rc;
-        if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
-            if ((rc = prof_begin(c, HOP_KERNEL_GRAD, 0.0))) return rc;
-            HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, c->opts.lr, c->stream));
-            if ((rc = prof_end(c))) return rc;
-        }
-        for (int p = jb; p < jb + nj; ++p) {
-            int e = s->wave_order[p];
-            c->version[s->worker[e]] = s->kind[e] == HOP_STEP ? s->iter[e] + 1 : s->iter[e];
-        }
-        c->next_wave = w + 1;
+    int rc;
+    if (c->use_graph && !c->profiling && wave_begin == 0 && wave_end == s->n_waves && s->n_waves > 0) {
+        if (!s->graph_exec || s->graph_epoch != c->epoch || s->graph_mode != c->grad_mode)
+            if ((rc = capture_graph(c, s)) != HOP_OK) return rc;
+        HOP_HIP(c, hipGraphLaunch((hipGraphExec_t)s->graph_exec, (hipStream_t)c->stream));
+    } else if ((rc = launch_waves(c, s, wave_begin, wave_end, c->stream, c->profiling)) != HOP_OK) {
+        return rc;
     }
+    for (int p = s->wave_begin[wave_begin]; p < s->wave_begin[wave_end]; ++p) {
+        int e = s->wave_order[p];
+        c->version[s->worker[e]] = s->kind[e] == HOP_STEP ? s->iter[e] + 1 : s->iter[e];
+    }
+    c->next_wave = wave_end;
+    return HOP_OK;
+}
+
+int hop_use_graph(hop_ctx* c, int enable) {
+    if (!c) return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    c->use_graph = enable != 0;
     return HOP_OK;
 }
 

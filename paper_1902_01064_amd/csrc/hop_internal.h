@@ -75,6 +75,9 @@ struct hop_schedule {
     std::vector<int32_t> grad_begin;    // n_waves + 1 offsets into grad_dev
     std::vector<double> wave_mix_bytes; // algorithmic bytes of each wave's mix launch
     std::vector<double> wave_grad_bytes;
+    void* graph_exec = nullptr;         // hipGraphExec_t of waves [0, n_waves), see hop_use_graph()
+    uint64_t graph_epoch = 0;
+    int graph_mode = -1;
 };
 
 // ---- context -----------------------------------------------------------------------
@@ -119,6 +122,8 @@ struct hop_ctx {
     const hop_schedule* running = nullptr;
     int next_wave = 0;
     bool profiling = false;
+    bool use_graph = false;
+    void* capture_stream = nullptr;     // library-owned stream used only to record graphs
     HopProfile prof;
     std::string last_error;
 };

@@ -159,6 +159,15 @@ __global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jo
     } else if (MAP == 0) {
         j = (int)(blockIdx.x / n_chunks);
         chunk = blockIdx.x % n_chunks;
+    } else if (MAP == 3) {
+        // every XCD owns one contiguous eighth of the columns
+        int64_t b = blockIdx.x;
+        int xcd = (int)(b % kXcd);
+        int64_t local = b / kXcd;
+        int64_t per_xcd = (n_chunks + kXcd - 1) / kXcd;
+        j = (int)(local % n_jobs);
+        chunk = xcd * per_xcd + local / n_jobs;
+        if (local / n_jobs >= per_xcd || chunk >= n_chunks) return;
     } else {
         j = (int)(blockIdx.x % n_jobs);
         chunk = blockIdx.x / n_jobs;
@@ -199,7 +208,7 @@ int launch_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
     int64_t per = (int64_t)T * VEC;
     int64_t n_chunks = (n4 + per - 1) / per;
     if (n_chunks < 1) n_chunks = 1;
-    int64_t grid = MAP == 1 ? grid_for(n_jobs, n_chunks) : n_chunks * n_jobs;
+    int64_t grid = (MAP == 1 || MAP == 3) ? grid_for(n_jobs, n_chunks) : n_chunks * n_jobs;
     if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((mix_kernel<VEC, NT, MAP, T>), dim3((unsigned)grid), dim3(T), 0, (hipStream_t)stream,
                        jobs_dev, n_jobs, d, n_chunks);
@@ -485,6 +494,8 @@ int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
         case 12: return launch_mix<2, 1, 1, 128>(jobs_dev, n_jobs, d, stream);
         case 13: return launch_mix<4, 1, 1, 128>(jobs_dev, n_jobs, d, stream);
         case 14: return launch_mix<1, 1, 1, 512>(jobs_dev, n_jobs, d, stream);
+        case 15: return launch_mix<4, 1, 3, 256>(jobs_dev, n_jobs, d, stream);
+        case 16: return launch_mix<2, 1, 3, 256>(jobs_dev, n_jobs, d, stream);
         default: break;
     }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = [
     "hop_set_grad_source", "hop_simulate", "hop_schedule_view", "hop_schedule_free", "hop_step",
     "hop_params", "hop_slot", "hop_coef", "hop_profile", "hop_profile_read", "hop_mix",
     "hop_grad_scratch_floats", "hop_svm_grad_dense", "hop_svm_grad_csr", "hop_synth_grad", "hop_copy",
-    "hop_download",
+    "hop_download", "hop_use_graph",
 ]
 
 
@@ -115,6 +115,7 @@ def load():
         "hop_slot": (C.c_int, [vp, i32, i32, C.POINTER(vp)]),
         "hop_coef": (C.c_int, [vp, vp, i32, C.POINTER(vp)]),
         "hop_profile": (C.c_int, [vp, C.c_int]),
+        "hop_use_graph": (C.c_int, [vp, C.c_int]),
         "hop_profile_read": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64),
                                        C.POINTER(C.c_double)]),
         "hop_mix": (C.c_int, [C.POINTER(hop_mix_job), i32, i64, vp]),
@@ -297,6 +298,10 @@ def hop_coef(ctx, sched, record):
     p = C.c_void_p()
     _check(load().hop_coef(ctx, sched.handle, record, C.byref(p)), "hop_coef")
     return p.value
+
+
+def hop_use_graph(ctx, enable):
+    _check(load().hop_use_graph(ctx, int(enable)), "hop_use_graph")
 
 
 def hop_profile(ctx, enable):

@@ -247,3 +247,41 @@ def test_cfg4_full_size_sampled_columns():
         assert worst <= RUN_TOL
     finally:
         sess.close()
+
+
+@pytest.mark.parametrize("cfgn,over,exact", [(1, dict(), True), (4, dict(d=(1 << 14) + 8, K=40), True),
+                                            (3, dict(d=1 << 13, rows=512, K=25), False)])
+def test_graph_replay_equals_kernel_by_kernel(cfgn, over, exact):
+    """hop_use_graph: the recorded graph is replayed several times, with other GPU work and
+    synchronisations in between, and every replay must leave the rings exactly as the same pass run
+    kernel by kernel does (CSR scatters use atomics, so there to rounding)."""
+    c = inputs.config(cfgn, **over)
+    p0, data = make_data(c)
+    snaps = {}
+    for mode in ("eager", "graph"):
+        sess = Session(c)
+        try:
+            attach(sess, c, p0, data)
+            sess.simulate()
+            hop.hop_use_graph(sess.ctx, int(mode == "graph"))
+            snaps[mode] = []
+            for rep in range(4):
+                sess.step()
+                sess.sync()
+                snaps[mode].append(sess.ring_snapshot())
+                junk = torch.randn(1 << 16, device=sess.dev)          # unrelated eager work between replays
+                junk = (junk * 2).sum()
+                sess.sync()
+                if rep == 1:                                          # a partial, kernel-by-kernel pass in between
+                    sess.step(0, 1)
+                    sess.step(1, -1)
+                    sess.sync()
+                    snaps[mode].append(sess.ring_snapshot())
+        finally:
+            sess.close()
+    assert len(snaps["eager"]) == len(snaps["graph"]) == 5
+    for a, b in zip(snaps["eager"], snaps["graph"]):
+        if exact:
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+        else:
+            assert rel_err(b, a) <= 1e-5
