@@ -58,6 +58,22 @@ def torus(r, c):
     return nb
 
 
+def ring_based(n):
+    """Ring plus an edge from every node to the most distant one (Section 7.3.1, graph 2); n even."""
+    return [sorted({(i - 1) % n, (i + 1) % n, (i + n // 2) % n} - {i}) for i in range(n)]
+
+
+def double_ring(n):
+    """Two ring-based graphs of n/2 nodes joined node to node (Section 7.3.1, graph 3)."""
+    h = n // 2
+    half = ring_based(h)
+    nb = []
+    for side in (0, 1):
+        for i in range(h):
+            nb.append(sorted([j + side * h for j in half[i]] + [i + (1 - side) * h]))
+    return nb
+
+
 def complete(n):
     return [[j for j in range(n) if j != i] for i in range(n)]
 
