@@ -11,7 +11,12 @@ TEST INFRASTRUCTURE ONLY - see oracle/__init__.py.
                    Eq. 2; with everything accepted at tag k it is W itself.
   svm_subgradient  hinge-loss linear SVM minibatch subgradient
                    g = lambda w - (1/B) sum_{m: y_m <x_m, w> < 1} y_m x_m
-                   ("Compute", Figure "Standard Decentralized Training" step 1)
+                   ("Compute", Figure "Standard Decentralized Training" step 1);
+                   with loss="log" the log loss the paper's own runs use
+                   (Section 7.2): g = lambda w - (1/B) sum_m y_m x_m / (1 + exp(y_m <x_m, w>))
+  momentum         Section 7.2's momentum 0.9, as a local velocity per worker:
+                   v <- mu v + g, then x_{k+1} = sum_a w'_a x_a - eta v (the
+                   velocity is never sent or averaged; a jump leaves it alone)
   reduce_apply     x_{k+1,i} = sum_a w'_a x_a - eta g   (steps 2 and 3 there)
   execute          all records in sequence order over rings of D slots
 
@@ -45,21 +50,30 @@ def hinge_margins(Xb, yb, w):
     return yb.astype(np.float64) * (Xb.astype(np.float64) @ w.astype(np.float64))
 
 
-def svm_subgradient_dense(X, y, w, rows, lam, active=None):
+def loss_coefficients(yb, margins, B, loss, active=None):
+    """c_m with g = lambda w - sum_m c_m x_m.  Hinge: y_m / B where the margin is below 1 (or where
+    `active` says so), else 0.  Log loss: y_m / (B (1 + exp(margin)))."""
+    if loss == "log":
+        with np.errstate(over="ignore"):
+            return yb / (float(B) * (1.0 + np.exp(margins))), np.ones(len(yb), dtype=bool)
+    act = (margins < 1.0) if active is None else np.asarray(active, dtype=bool)
+    return np.where(act, yb, 0.0) / float(B), act
+
+
+def svm_subgradient_dense(X, y, w, rows, lam, active=None, loss="hinge"):
     """Returns (g fp64 [d], margins fp64 [B], active bool [B]).  `active`
-    overrides the indicator (used only to follow the other branch at a margin
-    within rounding of the kink)."""
+    overrides the hinge indicator (used only to follow the other branch at a
+    margin within rounding of the kink)."""
     Xb = X[rows].astype(np.float64)
     yb = y[rows].astype(np.float64)
     w64 = w.astype(np.float64)
     margins = yb * (Xb @ w64)
-    act = (margins < 1.0) if active is None else np.asarray(active, dtype=bool)
-    coef = np.where(act, yb, 0.0) / float(len(rows))
+    coef, act = loss_coefficients(yb, margins, len(rows), loss, active)
     g = float(lam) * w64 - Xb.T @ coef
     return g, margins, act
 
 
-def svm_subgradient_csr(rowptr, col, val, y, w, rows, lam, active=None):
+def svm_subgradient_csr(rowptr, col, val, y, w, rows, lam, active=None, loss="hinge"):
     """Same for CSR features (rowptr int64, col int32 ascending per row)."""
     w64 = w.astype(np.float64)
     B = len(rows)
@@ -67,12 +81,13 @@ def svm_subgradient_csr(rowptr, col, val, y, w, rows, lam, active=None):
     for m, r in enumerate(rows):
         lo, hi = int(rowptr[r]), int(rowptr[r + 1])
         margins[m] = float(y[r]) * float(np.dot(val[lo:hi].astype(np.float64), w64[col[lo:hi]]))
-    act = (margins < 1.0) if active is None else np.asarray(active, dtype=bool)
+    yb = np.array([float(y[r]) for r in rows], dtype=np.float64)
+    coef, act = loss_coefficients(yb, margins, B, loss, active)
     g = float(lam) * w64
     for m, r in enumerate(rows):
-        if act[m]:
+        if coef[m] != 0.0:
             lo, hi = int(rowptr[r]), int(rowptr[r + 1])
-            np.subtract.at(g, col[lo:hi], (float(y[r]) / B) * val[lo:hi].astype(np.float64))
+            np.subtract.at(g, col[lo:hi], coef[m] * val[lo:hi].astype(np.float64))
     return g, margins, act
 
 
@@ -103,23 +118,23 @@ class GradSynth:
 
 
 class GradSvmDense:
-    def __init__(self, seed, X, y, batch, lam):
-        self.seed, self.X, self.y, self.batch, self.lam = seed, X, y, batch, lam
+    def __init__(self, seed, X, y, batch, lam, loss="hinge"):
+        self.seed, self.X, self.y, self.batch, self.lam, self.loss = seed, X, y, batch, lam, loss
         self.log = {}
         self.force = {}            # (i, k) -> bool[B], see svm_subgradient_dense
 
     def __call__(self, i, k, w):
         rows = rng.batch_rows(self.seed, i, k, self.batch, self.X[i].shape[0])
         g, m, a = svm_subgradient_dense(self.X[i], self.y[i], w, rows, self.lam,
-                                        self.force.get((i, k)))
+                                        self.force.get((i, k)), self.loss)
         self.log[(i, k)] = (rows, m, a)
         return g
 
 
 class GradSvmCsr:
-    def __init__(self, seed, data, batch, lam):
+    def __init__(self, seed, data, batch, lam, loss="hinge"):
         """data[i] = (rowptr, col, val, y)"""
-        self.seed, self.data, self.batch, self.lam = seed, data, batch, lam
+        self.seed, self.data, self.batch, self.lam, self.loss = seed, data, batch, lam, loss
         self.log = {}
         self.force = {}
 
@@ -127,7 +142,7 @@ class GradSvmCsr:
         rowptr, col, val, y = self.data[i]
         rows = rng.batch_rows(self.seed, i, k, self.batch, len(rowptr) - 1)
         g, m, a = svm_subgradient_csr(rowptr, col, val, y, w, rows, self.lam,
-                                      self.force.get((i, k)))
+                                      self.force.get((i, k)), self.loss)
         self.log[(i, k)] = (rows, m, a)
         return g
 
@@ -141,22 +156,34 @@ def init_rings(p0, N, D):
     return rings
 
 
-def apply_record(rings, rec, grad, eta):
-    """Execute one record against the rings, in place; returns the new vector."""
+def momentum_step(vel_i, g, mu):
+    """v <- mu v + g in fp64 from the stored fp32 velocity; returns (fp64 value used by Apply, fp32
+    value stored).  g = None counts as a zero gradient."""
+    v64 = float(np.float32(mu)) * vel_i.astype(np.float64)
+    if g is not None:
+        v64 = v64 + np.asarray(g, dtype=np.float64)
+    return v64, v64.astype(np.float32)
+
+
+def apply_record(rings, rec, grad, eta, vel=None, mu=0.0):
+    """Execute one record against the rings, in place; returns the new vector.  vel: [N, d] fp32
+    velocities (updated in place by STEP records) when momentum is on."""
     vecs = [rings[j, sl] for j, sl in zip(rec.src_worker, rec.src_slot)]
     g = None
     if rec.kind == STEP:
         g = grad(rec.worker, rec.k, vecs[0])
+        if vel is not None:
+            g, vel[rec.worker] = momentum_step(vel[rec.worker], g, mu)
     out = reduce_apply(vecs, rec.w32, g, eta)
     rings[rec.worker, rec.out_slot] = out
     return out
 
 
-def execute(records, rings, grad, eta, on_record=None):
+def execute(records, rings, grad, eta, on_record=None, vel=None, mu=0.0):
     """Records in sequence order.  Returns version[i] = newest iteration held."""
     version = [0] * rings.shape[0]
     for rec in records:
-        out = apply_record(rings, rec, grad, eta)
+        out = apply_record(rings, rec, grad, eta, vel, mu)
         version[rec.worker] = rec.k + 1 if rec.kind == STEP else rec.k
         if on_record is not None:
             on_record(rec, out)

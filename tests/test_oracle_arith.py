@@ -193,3 +193,95 @@ def test_batch_rows_are_uniform_and_keyed_by_iteration():
     assert r.min() >= 0 and r.max() < 100
     assert np.abs(np.bincount(r, minlength=100) / len(r) - 0.01).max() < 0.004
     assert not np.array_equal(rng.batch_rows(1, 2, 5, 64, 100), rng.batch_rows(1, 2, 6, 64, 100))
+
+
+# ---- log loss (Section 7.2: "We use log loss for SVM instead of hinge loss") -------------------------
+def test_log_loss_gradient_matches_finite_differences_and_limits():
+    rs = np.random.default_rng(9)
+    rows_n, d, B, lam = 40, 25, 12, 0.03
+    X = rs.normal(size=(rows_n, d)).astype(np.float32)
+    y = np.sign(rs.normal(size=rows_n)).astype(np.float32)
+    w = (0.3 * rs.normal(size=d)).astype(np.float32)
+    rows = rs.integers(0, rows_n, size=B)
+    g, margins, _ = arith.svm_subgradient_dense(X, y, w, rows, lam, loss="log")
+    Xb, yb = X[rows].astype(np.float64), y[rows].astype(np.float64)
+
+    def loss(v):
+        return 0.5 * lam * v @ v + np.log1p(np.exp(-yb * (Xb @ v))).sum() / B
+    w64 = w.astype(np.float64)
+    for c in range(d):
+        e = np.zeros(d)
+        e[c] = 1e-6
+        assert abs((loss(w64 + e) - loss(w64 - e)) / 2e-6 - g[c]) < 1e-7
+    # far on the wrong side of the margin the log loss pulls like an active hinge sample, far on the
+    # right side not at all
+    c_neg, _ = arith.loss_coefficients(np.array([1.0, -1.0]), np.array([-50.0, -50.0]), 4, "log")
+    c_pos, _ = arith.loss_coefficients(np.array([1.0, -1.0]), np.array([800.0, 50.0]), 4, "log")
+    assert np.allclose(c_neg, [0.25, -0.25], rtol=1e-12) and np.all(np.abs(c_pos) < 1e-20)
+    # csr agrees with dense on the same matrix
+    wstar = inputs.hidden_w(3, 200)
+    rowptr, col, val, yy = [t.numpy() for t in inputs.csr_svm_data(3, 0, 64, 200, 7, 1.1, wstar)]
+    dense = np.zeros((64, 200), dtype=np.float32)
+    for r in range(64):
+        dense[r, col[rowptr[r]:rowptr[r + 1]]] = val[rowptr[r]:rowptr[r + 1]]
+    wv = inputs.initial_params(3, 200, 0.5).numpy()
+    rr = rng.batch_rows(3, 0, 1, 20, 64)
+    g1, _, _ = arith.svm_subgradient_csr(rowptr, col, val, yy, wv, rr, 1e-3, loss="log")
+    g2, _, _ = arith.svm_subgradient_dense(dense, yy, wv, rr, 1e-3, loss="log")
+    assert np.allclose(g1, g2, rtol=1e-12, atol=1e-15)
+
+
+# ---- momentum (Section 7.2: momentum 0.9) ------------------------------------------------------------
+def test_momentum_closed_forms():
+    nb = inputs.ring(4)
+    W = inputs.uniform_weights(nb)
+    N, d, K, eta, mu = 4, 6, 9, 0.05, 0.9
+    h, recs = _run(nb, W, 1, 0, K)
+    p0 = np.linspace(-1, 1, d).astype(np.float32)
+    gconst = np.linspace(0.5, -0.5, d)
+
+    class Const:
+        def __call__(self, i, k, w):
+            return gconst
+    # identical replicas + the same constant gradient everywhere: averaging is the identity, so
+    # x_K = x_0 - eta g sum_{t=1..K} (1 - mu^t) / (1 - mu)
+    rings = arith.init_rings(p0, N, h.D)
+    vel = np.zeros((N, d), dtype=np.float32)
+    ver = arith.execute(recs, rings, Const(), eta, vel=vel, mu=mu)
+    got = arith.final_params(rings, ver).astype(np.float64)
+    mu32, eta32 = float(np.float32(mu)), float(np.float32(eta))
+    geo = sum((1 - mu32 ** t) / (1 - mu32) for t in range(1, K + 1))
+    want = p0.astype(np.float64) - eta32 * gconst * geo
+    assert np.allclose(got, np.tile(want, (N, 1)), atol=2e-6)
+    assert np.allclose(vel, np.tile(gconst * (1 - mu32 ** K) / (1 - mu32), (N, 1)), atol=1e-6)
+    # mu = 0 is the plain update, bit for bit
+    r1 = arith.init_rings(p0, N, h.D)
+    r2 = arith.init_rings(p0, N, h.D)
+    arith.execute(recs, r1, Const(), eta)
+    arith.execute(recs, r2, Const(), eta, vel=np.zeros((N, d), dtype=np.float32), mu=0.0)
+    assert np.array_equal(r1, r2)
+
+
+def test_momentum_standard_mode_equals_dense_recurrence():
+    """V_{k+1} = mu V_k + G_k, X_{k+1} = W^T X_k - eta V_{k+1} with numpy, under random delays."""
+    nb = inputs.ring_with_chords(6, 1, 4)
+    W = inputs.metropolis_weights(nb)
+    N, d, K, B, lam, eta, mu, seed = 6, 30, 10, 8, 1e-2, 0.05, 0.9, 5
+    X, y, p0 = _svm_problem(N, 64, d, seed)
+    h, recs = _run(nb, W, 0, 0, K, seed=seed, delay_kind=rng.DELAY_EXP1, mult=[1, 2, 1, 1, 3, 1])
+    rings = arith.init_rings(p0, N, h.D)
+    vel = np.zeros((N, d), dtype=np.float32)
+    ver = arith.execute(recs, rings, arith.GradSvmDense(seed, X, y, B, lam, loss="log"), eta, vel=vel, mu=mu)
+    got = arith.final_params(rings, ver).astype(np.float64)
+    Xk = np.tile(p0.astype(np.float64), (N, 1))
+    Vk = np.zeros_like(Xk)
+    W64, mu32, eta32 = W.astype(np.float64), float(np.float32(mu)), float(np.float32(eta))
+    for k in range(K):
+        G = np.zeros_like(Xk)
+        for i in range(N):
+            rows = [rng.mix(seed, rng.STREAM_BATCH, i, k, m) % 64 for m in range(B)]
+            Xb, yb = X[i][rows].astype(np.float64), y[i][rows].astype(np.float64)
+            G[i] = lam * Xk[i] - (Xb * (yb / (1 + np.exp(yb * (Xb @ Xk[i]))))[:, None]).sum(0) / B
+        Vk = mu32 * Vk + G
+        Xk = W64.T @ Xk - eta32 * Vk
+    assert np.max(np.abs(got - Xk)) <= 3e-6 * np.max(np.abs(Xk))
