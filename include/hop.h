@@ -77,6 +77,9 @@ enum {
 
 enum { HOP_STEP = 0, HOP_JUMP = 1 };
 
+/* Loss of the linear SVM: hinge, or the log loss the paper's own runs use (Section 7.2). */
+enum { HOP_LOSS_HINGE = 0, HOP_LOSS_LOG = 1 };
+
 enum { HOP_KERNEL_MIX = 0, HOP_KERNEL_GRAD = 1, HOP_KERNEL_SYNTH = 2, HOP_KERNEL_COUNT = 3 };
 
 typedef struct hop_ctx hop_ctx;             /* opaque, owned by the library */
@@ -105,8 +108,11 @@ typedef struct {
     float lr;                     /* eta */
     float lambda;                 /* L2 coefficient of the SVM */
     int32_t batch;                /* minibatch size B, 0 = no data */
-    int32_t reserved;
+    int32_t loss;                 /* HOP_LOSS_* */
     uint64_t seed;
+    float momentum;               /* mu in [0, 1): v <- mu v + g, x <- reduce - eta v per worker (Section 7.2
+                                     uses 0.9); 0 = plain SGD, no velocity buffers */
+    int32_t reserved;
 } hop_opts;
 
 typedef struct {
@@ -144,7 +150,8 @@ typedef struct {
 } hop_schedule_arrays;
 
 /* One fused Reduce + Apply:  out[c] = sum_{a<A} w[a] * src[a][c] - eta * g[c]  for c < d.
- * g may be NULL (a jump's Reduce, Section 5).  out may alias none of src. */
+ * g may be NULL (a jump's Reduce, Section 5).  out may alias none of src.  With vel != NULL the
+ * velocity is updated in place first, vel[c] = mu * vel[c] + g[c], and takes g's place in Apply. */
 typedef struct {
     float* out;                   /* device */
     const float* g;               /* device or NULL */
@@ -152,13 +159,15 @@ typedef struct {
     int32_t A;                    /* 1 .. HOP_MAX_A */
     const float* src[HOP_MAX_A];  /* device */
     float w[HOP_MAX_A];
+    float* vel;                   /* device or NULL */
+    float mu;
 } hop_mix_job;
 
 const char* hop_strerror(int code);
 int hop_version(void);
 
 /* Fills *o with the defaults (max_ig 0, skip off, max_skip 10, trigger 1, lr 0.01, lambda 1e-4,
- * batch 0, seed 0). */
+ * batch 0, hinge loss, seed 0, momentum 0). */
 int hop_opts_default(hop_opts* o);
 
 /* Ring depth D and slot stride (in floats) used for N workers of d parameters under staleness bound
@@ -225,24 +234,25 @@ int hop_coef(hop_ctx* ctx, const hop_schedule* s, int32_t record, const float** 
 /* Per-kernel timing with HIP events on the context's stream.  hop_profile_read synchronises the
  * stream and returns, for launches since the last read: total milliseconds, number of launches and
  * the algorithmic bytes those launches had to move (for HOP_KERNEL_MIX: 4 d (A + 2) per STEP,
- * 4 d (A + 1) per JUMP or gradient-free STEP). */
+ * 4 d (A + 1) per JUMP or gradient-free STEP, 8 d more where a velocity is read and written). */
 int hop_profile(hop_ctx* ctx, int enable);
 int hop_profile_read(hop_ctx* ctx, int kernel, double* ms, int64_t* launches, double* bytes);
 
 /* Stand-alone kernels on caller-supplied device memory (same code the schedule runs). */
 /* Fused Reduce + Apply for n_jobs independent jobs (host array), each over d columns. */
 int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* hip_stream);
-/* Hinge-loss SVM minibatch subgradient g = lambda w - sum_m c_m x_{r_m}, c_m = y/B if
- * y <x, w> < 1 else 0; rows_dev holds B sample ids (device int32).  coef (device, B floats) receives
- * c_m.  scratch: device, hop_grad_scratch_floats(d, B) floats. */
+/* Linear-SVM minibatch (sub)gradient g = lambda w - sum_m c_m x_{r_m}; hinge: c_m = y/B if
+ * y <x, w> < 1 else 0; log loss: c_m = y / (B (1 + exp(y <x, w>))).  rows_dev holds B sample ids
+ * (device int32).  coef (device, B floats) receives c_m.  scratch: device,
+ * hop_grad_scratch_floats(d, B) floats. */
 int64_t hop_grad_scratch_floats(int64_t d, int32_t B);
 int hop_svm_grad_dense(const float* X, const float* y, const float* w, const int32_t* rows_dev,
-                       int32_t B, int64_t d, float lambda, float* g, float* coef, float* scratch,
-                       void* hip_stream);
+                       int32_t B, int64_t d, float lambda, int32_t loss, float* g, float* coef,
+                       float* scratch, void* hip_stream);
 /* Same on CSR features; g (device, d floats) receives the dense gradient. */
 int hop_svm_grad_csr(const int64_t* rowptr, const int32_t* col, const float* val, const float* y,
                      const float* w, const int32_t* rows_dev, int32_t B, int64_t d, float lambda,
-                     float* g, float* coef, void* hip_stream);
+                     int32_t loss, float* g, float* coef, void* hip_stream);
 /* Synthetic gradient of (seed, worker, iteration): centred sum of 12 hashed bytes per element times
  * sqrt(variance / 65535). */
 int hop_synth_grad(uint64_t seed, int32_t worker, int32_t iter, float variance, float* g, int64_t d,

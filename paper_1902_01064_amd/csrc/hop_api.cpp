@@ -134,8 +134,14 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                     gj.col = dd.col;
                     gj.val = dd.val;
                     gj.y = dd.y;
-                    // lambda w folds into the self term: sum_a w'_a x_a - eta lambda x_self - eta (sparse part)
-                    mj.w[0] = mj.w[0] - eta * c->opts.lambda;
+                    if (c->vel) {
+                        // a velocity is dense, so the gradient is materialised: g = lambda w, sparse part added
+                        gj.out = gj.g;
+                        mj.g = gj.g;
+                    } else {
+                        // lambda w folds into the self term: sum_a w'_a x_a - eta lambda x_self - eta (sparse part)
+                        mj.w[0] = mj.w[0] - eta * c->opts.lambda;
+                    }
                 } else if (mode == HOP_GRAD_SYNTH) {
                     hoprng::synth_keys(c->opts.seed, i, s->iter[e], &gj.k0, &gj.k1, &gj.k2);
                     gj.scale = hoprng::synth_scale(c->synth_variance);
@@ -146,8 +152,12 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                     want_job = false;
                 }
                 if (want_job) grad.push_back(gj);
+                if (c->vel && mj.g) {
+                    mj.vel = c->vel + (int64_t)i * c->stride;
+                    mj.mu = c->opts.momentum;
+                }
             }
-            s->wave_mix_bytes[w] += 4.0 * (double)c->d * (mj.A + 1 + (mj.g ? 1 : 0));
+            s->wave_mix_bytes[w] += 4.0 * (double)c->d * (mj.A + 1 + (mj.g ? 1 : 0) + (mj.vel ? 2 : 0));
         }
         s->grad_begin[w + 1] = (int32_t)grad.size();
     }
@@ -245,7 +255,9 @@ int hop_opts_default(hop_opts* o) {
     o->lr = 0.01f;
     o->lambda = 1e-4f;
     o->batch = 0;
+    o->loss = HOP_LOSS_HINGE;
     o->seed = 0;
+    o->momentum = 0.f;
     return HOP_OK;
 }
 
@@ -263,6 +275,7 @@ size_t hop_arena_bytes(int32_t N, int64_t d, int32_t s, const hop_opts* o) {
     if (N < 1 || hop_layout(d, s, o, &D, &stride) != HOP_OK) return 0;
     int batch = o ? o->batch : 0;
     int64_t floats = (int64_t)N * D * stride + (int64_t)N * stride + (int64_t)N * partial_floats(d, batch);
+    if (o && o->momentum > 0.f) floats += (int64_t)N * stride;
     return (size_t)floats * sizeof(float);
 }
 
@@ -276,7 +289,8 @@ int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64
     hop_opts o;
     hop_opts_default(&o);
     if (opts) o = *opts;
-    if (o.max_ig < 0 || o.max_skip < 1 || o.trigger < 0 || o.batch < 0 || o.batch > kMaxBatch)
+    if (o.max_ig < 0 || o.max_skip < 1 || o.trigger < 0 || o.batch < 0 || o.batch > kMaxBatch ||
+        (o.loss != HOP_LOSS_HINGE && o.loss != HOP_LOSS_LOG) || !(o.momentum >= 0.f && o.momentum < 1.f))
         return HOP_ERR_INVALID_ARG;
     hop_ctx* c = new (std::nothrow) hop_ctx();
     if (!c) return HOP_ERR_NOMEM;
@@ -329,6 +343,7 @@ int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64
             c->ring = (float*)dev->arena;
             c->gbuf = c->ring + (int64_t)N * c->D * c->stride;
             c->partial = c->gbuf + (int64_t)N * c->stride;
+            c->vel = o.momentum > 0.f ? c->partial + (int64_t)N * partial_floats(d, o.batch) : nullptr;
         }
     }
     if (rc != HOP_OK) {
@@ -358,6 +373,7 @@ int hop_set_params(hop_ctx* c, const float* p0, int per_worker, int on_device) {
         HOP_HIP(c, hipMemcpyAsync(slot_ptr(c, i, 0), src, (size_t)c->d * sizeof(float),
                                   on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, st));
     }
+    if (c->vel) HOP_HIP(c, hipMemsetAsync(c->vel, 0, (size_t)c->N * c->stride * sizeof(float), st));
     if (!on_device) HOP_HIP(c, hipStreamSynchronize(st));   // p0 is only borrowed for the call
     std::fill(c->version.begin(), c->version.end(), 0);
     c->running = nullptr;
@@ -493,17 +509,18 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
         } else if (ng > 0 && mode == HOP_GRAD_SVM_DENSE) {
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
             HOP_LAUNCH(c, hopk_dense_margin(gj, ng, B, c->d, stream));
-            HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, stream));
+            HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, c->opts.loss, stream));
             if (timed && (rc = prof_end(c))) return rc;
         } else if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
-            HOP_LAUNCH(c, hopk_csr_margin(gj, ng, B, stream));
+            HOP_LAUNCH(c, hopk_csr_margin(gj, ng, B, c->opts.loss, stream));
+            if (c->vel) HOP_LAUNCH(c, hopk_csr_dense_grad(gj, ng, B, c->d, c->opts.lambda, stream));
             if (timed && (rc = prof_end(c))) return rc;
         }
         if (timed && (rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
         HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, stream));
         if (timed && (rc = prof_end(c))) return rc;
-        if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
+        if (ng > 0 && mode == HOP_GRAD_SVM_CSR && !c->vel) {
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, 0.0))) return rc;
             HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, c->opts.lr, stream));
             if (timed && (rc = prof_end(c))) return rc;
@@ -638,8 +655,11 @@ int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* stream) {
             return HOP_ERR_INVALID_ARG;
         HopMixJob& mj = host[j];
         std::memset(&mj, 0, sizeof(mj));
+        if (in.vel && (!aligned16(in.vel) || !(in.mu >= 0.f))) return HOP_ERR_INVALID_ARG;
         mj.out = in.out;
         mj.g = in.g;
+        mj.vel = in.vel;
+        mj.mu = in.mu;
         mj.eta = in.eta;
         mj.A = in.A;
         for (int a = 0; a < in.A; ++a) {
@@ -666,7 +686,7 @@ int64_t hop_grad_scratch_floats(int64_t d, int32_t B) {
     return partial_floats(d, B);
 }
 
-static int run_one_grad(const HopGradJob& gj, int kind, int B, int64_t d, float lambda, void* stream) {
+static int run_one_grad(const HopGradJob& gj, int kind, int B, int64_t d, float lambda, int loss, void* stream) {
     HopGradJob* dev = nullptr;
     HOP_HIP(nullptr, hipMalloc((void**)&dev, sizeof(HopGradJob)));
     hipError_t e = hipMemcpy(dev, &gj, sizeof(HopGradJob), hipMemcpyHostToDevice);
@@ -674,9 +694,9 @@ static int run_one_grad(const HopGradJob& gj, int kind, int B, int64_t d, float 
     if (e == hipSuccess) {
         if (kind == HOP_GRAD_SVM_DENSE) {
             rc = hopk_dense_margin(dev, 1, B, d, stream);
-            if (!rc) rc = hopk_dense_grad(dev, 1, B, d, lambda, stream);
+            if (!rc) rc = hopk_dense_grad(dev, 1, B, d, lambda, loss, stream);
         } else if (kind == HOP_GRAD_SVM_CSR) {
-            rc = hopk_csr_margin(dev, 1, B, stream);
+            rc = hopk_csr_margin(dev, 1, B, loss, stream);
             if (!rc) rc = hopk_csr_dense_grad(dev, 1, B, d, lambda, stream);
         } else {
             rc = hopk_synth(dev, 1, d, stream);
@@ -691,26 +711,29 @@ static int run_one_grad(const HopGradJob& gj, int kind, int B, int64_t d, float 
 }
 
 int hop_svm_grad_dense(const float* X, const float* y, const float* w, const int32_t* rows_dev, int32_t B,
-                       int64_t d, float lambda, float* g, float* coef, float* scratch, void* stream) {
-    if (!X || !y || !w || !rows_dev || !g || !coef || !scratch || B < 1 || B > kMaxBatch || d < 1)
+                       int64_t d, float lambda, int32_t loss, float* g, float* coef, float* scratch,
+                       void* stream) {
+    if (!X || !y || !w || !rows_dev || !g || !coef || !scratch || B < 1 || B > kMaxBatch || d < 1 ||
+        (loss != HOP_LOSS_HINGE && loss != HOP_LOSS_LOG))
         return HOP_ERR_INVALID_ARG;
     if (d % 4 == 0 && (!aligned16(X) || !aligned16(w) || !aligned16(g))) return HOP_ERR_INVALID_ARG;
     HopGradJob gj;
     std::memset(&gj, 0, sizeof(gj));
     gj.X = X; gj.y = y; gj.w = w; gj.rows = rows_dev; gj.g = g; gj.coef = coef; gj.partial = scratch;
-    return run_one_grad(gj, HOP_GRAD_SVM_DENSE, B, d, lambda, stream);
+    return run_one_grad(gj, HOP_GRAD_SVM_DENSE, B, d, lambda, loss, stream);
 }
 
 int hop_svm_grad_csr(const int64_t* rowptr, const int32_t* col, const float* val, const float* y, const float* w,
-                     const int32_t* rows_dev, int32_t B, int64_t d, float lambda, float* g, float* coef,
-                     void* stream) {
-    if (!rowptr || !col || !val || !y || !w || !rows_dev || !g || !coef || B < 1 || B > kMaxBatch || d < 1)
+                     const int32_t* rows_dev, int32_t B, int64_t d, float lambda, int32_t loss, float* g,
+                     float* coef, void* stream) {
+    if (!rowptr || !col || !val || !y || !w || !rows_dev || !g || !coef || B < 1 || B > kMaxBatch || d < 1 ||
+        (loss != HOP_LOSS_HINGE && loss != HOP_LOSS_LOG))
         return HOP_ERR_INVALID_ARG;
     HopGradJob gj;
     std::memset(&gj, 0, sizeof(gj));
     gj.rowptr = rowptr; gj.col = col; gj.val = val; gj.y = y; gj.w = w; gj.rows = rows_dev;
     gj.g = g; gj.out = g; gj.coef = coef;
-    return run_one_grad(gj, HOP_GRAD_SVM_CSR, B, d, lambda, stream);
+    return run_one_grad(gj, HOP_GRAD_SVM_CSR, B, d, lambda, loss, stream);
 }
 
 int hop_synth_grad(uint64_t seed, int32_t worker, int32_t iter, float variance, float* g, int64_t d, void* stream) {
@@ -720,7 +743,7 @@ int hop_synth_grad(uint64_t seed, int32_t worker, int32_t iter, float variance, 
     gj.g = g;
     hoprng::synth_keys(seed, worker, iter, &gj.k0, &gj.k1, &gj.k2);
     gj.scale = hoprng::synth_scale(variance);
-    return run_one_grad(gj, HOP_GRAD_SYNTH, 0, d, 0.f, stream);
+    return run_one_grad(gj, HOP_GRAD_SYNTH, 0, d, 0.f, HOP_LOSS_HINGE, stream);
 }
 
 int hop_copy(void* dst, const void* src, size_t bytes, void* stream) {

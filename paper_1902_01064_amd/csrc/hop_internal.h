@@ -12,9 +12,11 @@
 struct alignas(16) HopMixJob {
     float* out;
     const float* g;            // null: no gradient term
+    float* vel;                // null: no momentum; else v <- mu v + g in place, Apply uses v
     float eta;
     int32_t A;
-    int32_t pad0, pad1;
+    float mu;
+    int32_t pad0;
     const float* src[HOP_MAX_A];
     float w[HOP_MAX_A];
 };
@@ -40,8 +42,8 @@ struct alignas(16) HopGradJob {
 int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream);
 int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream);
 int hopk_dense_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, void* stream);
-int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream);
-int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, void* stream);
+int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, int loss, void* stream);
+int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, void* stream);
 int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float eta, void* stream);
 int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream);
 int hopk_copy(void* dst, const void* src, size_t bytes, void* stream);
@@ -113,6 +115,7 @@ struct hop_ctx {
     float* ring = nullptr;              // N x D x stride
     float* gbuf = nullptr;              // N x stride
     float* partial = nullptr;           // N x batch x nseg
+    float* vel = nullptr;               // N x stride velocities, only with momentum
     std::vector<HopData> data;
     int grad_mode = HOP_GRAD_ZERO;
     float synth_variance = 0.f;

@@ -68,10 +68,12 @@ __device__ __forceinline__ void st_once(float* p, int64_t i, float4 v) {
     if (NT >= 1) st4_stream(p, i, v); else st4(p, i, v);
 }
 
-template <int A, int VEC, int NT, int T>
+template <int A, int VEC, int NT, int T, bool MOM>
 __device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int64_t first4, int64_t n4) {
     const float* g = job->g;
     const float neg_eta = -job->eta;
+    float* vel = job->vel;
+    const float mu = job->mu;
     float* out = job->out;
     float4 acc[VEC];
     int64_t idx[VEC];
@@ -103,7 +105,20 @@ __device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int6
             acc[u].w = fmaf(wa, v.w, acc[u].w);
         }
     }
-    if (g != nullptr) {
+    if (MOM) {
+        // v <- mu v + g (a missing g counts as zero), Apply with the new velocity
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) {
+            float4 v = ok[u] ? ld_once<NT>(vel, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 gg = (ok[u] && g != nullptr) ? ld_once<NT>(g, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            v = make_float4(fmaf(mu, v.x, gg.x), fmaf(mu, v.y, gg.y), fmaf(mu, v.z, gg.z), fmaf(mu, v.w, gg.w));
+            if (ok[u]) st_once<NT>(vel, idx[u], v);
+            acc[u].x = fmaf(neg_eta, v.x, acc[u].x);
+            acc[u].y = fmaf(neg_eta, v.y, acc[u].y);
+            acc[u].z = fmaf(neg_eta, v.z, acc[u].z);
+            acc[u].w = fmaf(neg_eta, v.w, acc[u].w);
+        }
+    } else if (g != nullptr) {
 #pragma unroll
         for (int u = 0; u < VEC; ++u) {
             float4 v = ok[u] ? ld_once<NT>(g, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -138,8 +153,16 @@ __device__ __forceinline__ void mix_tile_any(const HopMixJob* __restrict__ job, 
             acc.z = fmaf(w, v.z, acc.z);
             acc.w = fmaf(w, v.w, acc.w);
         }
-        if (g != nullptr) {
+        if (job->vel != nullptr) {
+            float4 gg = g != nullptr ? ld_once<NT>(g, i) : make_float4(0.f, 0.f, 0.f, 0.f);
+            v = ld_once<NT>(job->vel, i);
+            const float mu = job->mu;
+            v = make_float4(fmaf(mu, v.x, gg.x), fmaf(mu, v.y, gg.y), fmaf(mu, v.z, gg.z), fmaf(mu, v.w, gg.w));
+            st_once<NT>(job->vel, i, v);
+        } else if (g != nullptr) {
             v = ld_once<NT>(g, i);
+        }
+        if (job->vel != nullptr || g != nullptr) {
             acc.x = fmaf(neg_eta, v.x, acc.x);
             acc.y = fmaf(neg_eta, v.y, acc.y);
             acc.z = fmaf(neg_eta, v.z, acc.z);
@@ -175,20 +198,38 @@ __global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jo
     const HopMixJob* job = jobs + j;
     const int64_t n4 = d >> 2;
     const int64_t first4 = chunk * (int64_t)(T * VEC);
-    switch (job->A) {
-        case 1: mix_tile<1, VEC, NT, T>(job, first4, n4); break;
-        case 2: mix_tile<2, VEC, NT, T>(job, first4, n4); break;
-        case 3: mix_tile<3, VEC, NT, T>(job, first4, n4); break;
-        case 4: mix_tile<4, VEC, NT, T>(job, first4, n4); break;
-        case 5: mix_tile<5, VEC, NT, T>(job, first4, n4); break;
-        case 6: mix_tile<6, VEC, NT, T>(job, first4, n4); break;
-        case 7: mix_tile<7, VEC, NT, T>(job, first4, n4); break;
-        case 8: mix_tile<8, VEC, NT, T>(job, first4, n4); break;
-        case 9: mix_tile<9, VEC, NT, T>(job, first4, n4); break;
-        case 10: mix_tile<10, VEC, NT, T>(job, first4, n4); break;
-        case 11: mix_tile<11, VEC, NT, T>(job, first4, n4); break;
-        case 12: mix_tile<12, VEC, NT, T>(job, first4, n4); break;
-        default: mix_tile_any<VEC, NT, T>(job, first4, n4); break;
+    if (job->vel != nullptr) {
+        switch (job->A) {
+            case 1: mix_tile<1, VEC, NT, T, true>(job, first4, n4); break;
+            case 2: mix_tile<2, VEC, NT, T, true>(job, first4, n4); break;
+            case 3: mix_tile<3, VEC, NT, T, true>(job, first4, n4); break;
+            case 4: mix_tile<4, VEC, NT, T, true>(job, first4, n4); break;
+            case 5: mix_tile<5, VEC, NT, T, true>(job, first4, n4); break;
+            case 6: mix_tile<6, VEC, NT, T, true>(job, first4, n4); break;
+            case 7: mix_tile<7, VEC, NT, T, true>(job, first4, n4); break;
+            case 8: mix_tile<8, VEC, NT, T, true>(job, first4, n4); break;
+            case 9: mix_tile<9, VEC, NT, T, true>(job, first4, n4); break;
+            case 10: mix_tile<10, VEC, NT, T, true>(job, first4, n4); break;
+            case 11: mix_tile<11, VEC, NT, T, true>(job, first4, n4); break;
+            case 12: mix_tile<12, VEC, NT, T, true>(job, first4, n4); break;
+            default: mix_tile_any<VEC, NT, T>(job, first4, n4); break;
+        }
+    } else {
+        switch (job->A) {
+            case 1: mix_tile<1, VEC, NT, T, false>(job, first4, n4); break;
+            case 2: mix_tile<2, VEC, NT, T, false>(job, first4, n4); break;
+            case 3: mix_tile<3, VEC, NT, T, false>(job, first4, n4); break;
+            case 4: mix_tile<4, VEC, NT, T, false>(job, first4, n4); break;
+            case 5: mix_tile<5, VEC, NT, T, false>(job, first4, n4); break;
+            case 6: mix_tile<6, VEC, NT, T, false>(job, first4, n4); break;
+            case 7: mix_tile<7, VEC, NT, T, false>(job, first4, n4); break;
+            case 8: mix_tile<8, VEC, NT, T, false>(job, first4, n4); break;
+            case 9: mix_tile<9, VEC, NT, T, false>(job, first4, n4); break;
+            case 10: mix_tile<10, VEC, NT, T, false>(job, first4, n4); break;
+            case 11: mix_tile<11, VEC, NT, T, false>(job, first4, n4); break;
+            case 12: mix_tile<12, VEC, NT, T, false>(job, first4, n4); break;
+            default: mix_tile_any<VEC, NT, T>(job, first4, n4); break;
+        }
     }
     // the d mod 4 trailing columns, one thread each, by the workgroup of the last chunk
     if (chunk == n_chunks - 1) {
@@ -196,7 +237,13 @@ __global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jo
         if (threadIdx.x < 4 && c < d) {
             float acc = job->w[0] * job->src[0][c];
             for (int a = 1; a < job->A; ++a) acc = fmaf(job->w[a], job->src[a][c], acc);
-            if (job->g != nullptr) acc = fmaf(-job->eta, job->g[c], acc);
+            if (job->vel != nullptr) {
+                float v = fmaf(job->mu, job->vel[c], job->g != nullptr ? job->g[c] : 0.f);
+                job->vel[c] = v;
+                acc = fmaf(-job->eta, v, acc);
+            } else if (job->g != nullptr) {
+                acc = fmaf(-job->eta, job->g[c], acc);
+            }
             job->out[c] = acc;
         }
     }
@@ -288,6 +335,13 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
     return t;                                          // thread 0 holds the sum
 }
 
+// c_m of g = lambda w - sum_m c_m x_m: hinge y/B where y <x, w> < 1, log loss y / (B (1 + e^{y <x, w>}))
+__device__ __forceinline__ float loss_coef(float y, float dot, float invB, int loss) {
+    const float m = y * dot;
+    if (loss == HOP_LOSS_LOG) return y * invB / (1.0f + expf(m));
+    return m < 1.0f ? y * invB : 0.f;
+}
+
 // ------------------------------------------------------------- dense SVM: margins ("Compute") ----
 // One workgroup per (job, minibatch row, column segment): partial <x_r, w> over 16384 columns.
 constexpr int kSegVec = 16;
@@ -335,7 +389,7 @@ constexpr int kRowUnroll = 8;
 
 __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* __restrict__ jobs, int n_jobs,
                                                               int B, int64_t d, int nseg, float lambda,
-                                                              int64_t n_chunks) {
+                                                              int loss, int64_t n_chunks) {
     __shared__ float coefS[kMaxB + kRowUnroll];
     __shared__ int rowS[kMaxB + kRowUnroll];
     __shared__ float allC[kMaxB];
@@ -348,8 +402,7 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
     for (int m = threadIdx.x; m < B; m += kThreads) {
         float dot = 0.f;
         for (int sg = 0; sg < nseg; ++sg) dot += job->partial[(int64_t)m * nseg + sg];
-        float y = job->y[job->rows[m]];
-        float c = (y * dot < 1.0f) ? y * invB : 0.f;
+        float c = loss_coef(job->y[job->rows[m]], dot, invB, loss);
         allC[m] = c;
         if (chunk == 0) job->coef[m] = c;
     }
@@ -416,7 +469,7 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
 // ------------------------------------------------------------------- CSR SVM: margins ----
 // One wavefront per (job, minibatch row): gather w[col], reduce across the 64 lanes.
 __global__ __launch_bounds__(kThreads) void csr_margin_kernel(const HopGradJob* __restrict__ jobs, int B,
-                                                              int rows_per_job_blocks) {
+                                                              int rows_per_job_blocks, int loss) {
     const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const HopGradJob* job = jobs + blockIdx.x / rows_per_job_blocks;
     const int m = (blockIdx.x % rows_per_job_blocks) * (kThreads / 64) + wv;
@@ -427,10 +480,7 @@ __global__ __launch_bounds__(kThreads) void csr_margin_kernel(const HopGradJob* 
     float acc = 0.f;
     for (int64_t p = lo + lane; p < hi; p += 64) acc = fmaf(job->val[p], w[job->col[p]], acc);
     acc = wave_sum(acc);
-    if (lane == 0) {
-        float y = job->y[r];
-        job->coef[m] = (y * acc < 1.0f) ? y * (1.0f / (float)B) : 0.f;
-    }
+    if (lane == 0) job->coef[m] = loss_coef(job->y[r], acc, 1.0f / (float)B, loss);
 }
 
 // target[col] += factor * c_m * val for the active rows (the sparse part of -eta g, or of g).
@@ -529,7 +579,8 @@ int hopk_dense_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, 
     return launch_status();
 }
 
-int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream) {
+int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, int loss,
+                    void* stream) {
     if (n_jobs <= 0 || B <= 0) return 0;
     if (B > kMaxB) return (int)hipErrorInvalidValue;
     int nseg = hopk_dense_nseg(d);
@@ -537,15 +588,15 @@ int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, fl
     int64_t grid = grid_for(n_jobs, n_chunks);
     if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(dense_grad_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev,
-                       n_jobs, B, d, nseg, lambda, n_chunks);
+                       n_jobs, B, d, nseg, lambda, loss, n_chunks);
     return launch_status();
 }
 
-int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, void* stream) {
+int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, void* stream) {
     if (n_jobs <= 0 || B <= 0) return 0;
     int per = (B + kThreads / 64 - 1) / (kThreads / 64);
     hipLaunchKernelGGL(csr_margin_kernel, dim3((unsigned)(n_jobs * per)), dim3(kThreads), 0, (hipStream_t)stream,
-                       jobs_dev, B, per);
+                       jobs_dev, B, per, loss);
     return launch_status();
 }
 

@@ -18,6 +18,7 @@ HOP_DELAY_NONE, HOP_DELAY_EXP1, HOP_DELAY_BERNOULLI6, HOP_DELAY_TABLE = 0, 1, 2,
 HOP_GRAD_ZERO, HOP_GRAD_SVM_DENSE, HOP_GRAD_SVM_CSR, HOP_GRAD_SYNTH, HOP_GRAD_EXTERNAL = 0, 1, 2, 3, 4
 HOP_STEP, HOP_JUMP = 0, 1
 HOP_KERNEL_MIX, HOP_KERNEL_GRAD, HOP_KERNEL_SYNTH = 0, 1, 2
+HOP_LOSS_HINGE, HOP_LOSS_LOG = 0, 1
 HOP_TICKS_NEVER = 1 << 62
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhop.so")
@@ -49,7 +50,8 @@ class hop_device(C.Structure):
 class hop_opts(C.Structure):
     _fields_ = [("max_ig", C.c_int32), ("skip_on", C.c_int32), ("max_skip", C.c_int32),
                 ("trigger", C.c_int32), ("lr", C.c_float), ("lambda_", C.c_float),
-                ("batch", C.c_int32), ("reserved", C.c_int32), ("seed", C.c_uint64)]
+                ("batch", C.c_int32), ("loss", C.c_int32), ("seed", C.c_uint64),
+                ("momentum", C.c_float), ("reserved", C.c_int32)]
 
 
 class hop_delay_model(C.Structure):
@@ -73,7 +75,8 @@ class hop_schedule_arrays(C.Structure):
 
 class hop_mix_job(C.Structure):
     _fields_ = [("out", C.c_void_p), ("g", C.c_void_p), ("eta", C.c_float), ("A", C.c_int32),
-                ("src", C.c_void_p * HOP_MAX_A), ("w", C.c_float * HOP_MAX_A)]
+                ("src", C.c_void_p * HOP_MAX_A), ("w", C.c_float * HOP_MAX_A),
+                ("vel", C.c_void_p), ("mu", C.c_float)]
 
 
 _lib = None
@@ -120,8 +123,8 @@ def load():
                                        C.POINTER(C.c_double)]),
         "hop_mix": (C.c_int, [C.POINTER(hop_mix_job), i32, i64, vp]),
         "hop_grad_scratch_floats": (i64, [i64, i32]),
-        "hop_svm_grad_dense": (C.c_int, [vp, vp, vp, vp, i32, i64, f32, vp, vp, vp, vp]),
-        "hop_svm_grad_csr": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i64, f32, vp, vp, vp]),
+        "hop_svm_grad_dense": (C.c_int, [vp, vp, vp, vp, i32, i64, f32, i32, vp, vp, vp, vp]),
+        "hop_svm_grad_csr": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i64, f32, i32, vp, vp, vp]),
         "hop_synth_grad": (C.c_int, [C.c_uint64, i32, i32, f32, vp, i64, vp]),
         "hop_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
         "hop_download": (C.c_int, [vp, vp, C.c_size_t, vp]),
@@ -150,11 +153,13 @@ def _np_i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
-def make_opts(max_ig=0, skip_on=False, max_skip=10, trigger=1, lr=0.01, lam=1e-4, batch=0, seed=0):
+def make_opts(max_ig=0, skip_on=False, max_skip=10, trigger=1, lr=0.01, lam=1e-4, batch=0, seed=0,
+              loss=HOP_LOSS_HINGE, momentum=0.0):
     o = hop_opts()
     _check(load().hop_opts_default(C.byref(o)), "hop_opts_default")
     o.max_ig, o.skip_on, o.max_skip, o.trigger = int(max_ig), int(bool(skip_on)), int(max_skip), int(trigger)
     o.lr, o.lambda_, o.batch, o.seed = float(lr), float(lam), int(batch), int(seed)
+    o.loss, o.momentum = int(loss), float(momentum)
     return o
 
 
@@ -322,6 +327,8 @@ def hop_mix(jobs, d, stream=0):
         arr[j].g = job.get("g") or None
         arr[j].eta = float(job.get("eta", 0.0))
         arr[j].A = len(job["src"])
+        arr[j].vel = job.get("vel") or None
+        arr[j].mu = float(job.get("mu", 0.0))
         for a, (p, w) in enumerate(zip(job["src"], job["w"])):
             if a < HOP_MAX_A:
                 arr[j].src[a] = p
@@ -333,13 +340,13 @@ def hop_grad_scratch_floats(d, B):
     return load().hop_grad_scratch_floats(d, B)
 
 
-def hop_svm_grad_dense(X, y, w, rows, B, d, lam, g, coef, scratch, stream=0):
-    _check(load().hop_svm_grad_dense(X, y, w, rows, B, d, lam, g, coef, scratch, C.c_void_p(stream)),
+def hop_svm_grad_dense(X, y, w, rows, B, d, lam, g, coef, scratch, stream=0, loss=HOP_LOSS_HINGE):
+    _check(load().hop_svm_grad_dense(X, y, w, rows, B, d, lam, loss, g, coef, scratch, C.c_void_p(stream)),
            "hop_svm_grad_dense")
 
 
-def hop_svm_grad_csr(rowptr, col, val, y, w, rows, B, d, lam, g, coef, stream=0):
-    _check(load().hop_svm_grad_csr(rowptr, col, val, y, w, rows, B, d, lam, g, coef, C.c_void_p(stream)),
+def hop_svm_grad_csr(rowptr, col, val, y, w, rows, B, d, lam, g, coef, stream=0, loss=HOP_LOSS_HINGE):
+    _check(load().hop_svm_grad_csr(rowptr, col, val, y, w, rows, B, d, lam, loss, g, coef, C.c_void_p(stream)),
            "hop_svm_grad_csr")
 
 

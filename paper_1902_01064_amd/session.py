@@ -15,7 +15,7 @@ class Session:
         torch.cuda.set_device(self.dev)
         self.opts = hop.make_opts(max_ig=c["max_ig"], skip_on=c["skip_on"], max_skip=c["max_skip"],
                                   trigger=c["trigger"], lr=c["lr"], lam=c["lam"], batch=c["batch"],
-                                  seed=c["seed"])
+                                  seed=c["seed"], loss=c.get("loss", 0), momentum=c.get("momentum", 0.0))
         self.N, self.d = c["N"], c["d"]
         need = hop.hop_arena_bytes(self.N, self.d, c["s"], self.opts)
         self.arena = torch.zeros(need // 4, dtype=torch.float32, device=self.dev)
@@ -39,6 +39,11 @@ class Session:
         """[N, D, d] numpy copy of every ring slot."""
         r = self.arena[: self.N * self.D * self.stride].view(self.N, self.D, self.stride)[:, :, : self.d]
         return r.cpu().numpy()
+
+    def vel_snapshot(self):
+        """[N, d] numpy copy of the velocities (contexts with momentum: the arena's last N slots)."""
+        v = self.arena[self.arena.numel() - self.N * self.stride:].view(self.N, self.stride)[:, : self.d]
+        return v.cpu().numpy()
 
     def params(self):
         out, its = [], []

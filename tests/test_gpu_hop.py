@@ -21,6 +21,7 @@ pytestmark = pytest.mark.gpu
 
 STEP_TOL = 1e-5
 RUN_TOL = 1e-4
+LOSS = {0: "hinge", 1: "log"}
 
 
 
@@ -74,11 +75,11 @@ def oracle_grad(c, data, cols=None):
     if c["model"] == "dense":
         X = [x.numpy() for x in data[0]]
         y = [t.numpy() for t in data[1]]
-        base = arith.GradSvmDense(c["seed"], X, y, c["batch"], c["lam"])
+        base = arith.GradSvmDense(c["seed"], X, y, c["batch"], c["lam"], LOSS[c.get("loss", 0)])
         return base, lambda i, rows, w: np.abs(X[i][rows].astype(np.float64) * w.astype(np.float64)).sum(1)
     if c["model"] == "csr":
         dn = [tuple(t.numpy() for t in dd) for dd in data]
-        base = arith.GradSvmCsr(c["seed"], dn, c["batch"], c["lam"])
+        base = arith.GradSvmCsr(c["seed"], dn, c["batch"], c["lam"], LOSS[c.get("loss", 0)])
 
         def scale(i, rows, w):
             rp, cn, vn, _ = dn[i]
@@ -111,12 +112,14 @@ def run_parity(c, per_wave_check=True):
         sched = sess.simulate()
         assert_schedule_equal(sched, h, recs)
         base, scale_of = oracle_grad(c, data)
-        has_hinge = c["model"] in ("dense", "csr")
+        has_hinge = c["model"] in ("dense", "csr") and c.get("loss", 0) == 0
+        mu = float(c.get("momentum", 0.0))
         worst_step = strict_step = 0.0
         gpu_active = {}
         # ---- every record on its own: oracle arithmetic on the GPU's own inputs of that wave ----
         for w in range(sched.n_waves):
             before = sess.ring_snapshot() if per_wave_check else None
+            vel_before = sess.vel_snapshot() if per_wave_check and mu > 0 else None
             sess.step(w, w + 1)
             sess.sync()
             members = [int(e) for e in sched.wave_order[sched.wave_begin[w]:sched.wave_begin[w + 1]]]
@@ -127,11 +130,15 @@ def run_parity(c, per_wave_check=True):
             if not per_wave_check:
                 continue
             after = sess.ring_snapshot()
+            vel_after = sess.vel_snapshot() if mu > 0 else None
             for e in members:
                 r = recs[e]
                 grad = FollowKernelAtTies(base, gpu_active, scale_of) if has_hinge else base
                 vecs = [before[j, sl] for j, sl in zip(r.src_worker, r.src_slot)]
                 g = grad(r.worker, r.k, vecs[0]) if r.kind == protocol.STEP else None
+                if mu > 0 and r.kind == protocol.STEP and c["model"] != "none":
+                    g, v32 = arith.momentum_step(vel_before[r.worker], g, mu)
+                    worst_step = max(worst_step, rel_err(vel_after[r.worker], v32))
                 ref = arith.reduce_apply(vecs, r.w32, g, c["lr"])
                 worst_step = max(worst_step, rel_err(after[r.worker, r.out_slot], ref))
                 strict_step = max(strict_step, strict_rel_err(after[r.worker, r.out_slot], ref))
@@ -139,10 +146,13 @@ def run_parity(c, per_wave_check=True):
         # ---- the run as a whole: the oracle from p0 in sequence order ----
         rings = arith.init_rings(p0.numpy(), c["N"], h.D)
         grad = FollowKernelAtTies(base, gpu_active, scale_of) if has_hinge else base
-        ver = arith.execute(recs, rings, grad, c["lr"])
+        vel = np.zeros((c["N"], c["d"]), dtype=np.float32) if mu > 0 else None
+        ver = arith.execute(recs, rings, grad, c["lr"], vel=vel, mu=mu)
         want = arith.final_params(rings, ver)
         got, its = sess.params()
         assert its == ver == [c["K"]] * c["N"]
+        if mu > 0:
+            assert rel_err(sess.vel_snapshot(), vel) <= RUN_TOL
         gotn = [got[i].cpu().numpy() for i in range(c["N"])]
         worst_run = max(rel_err(gotn[i], want[i]) for i in range(c["N"]))
         strict_run = max(strict_rel_err(gotn[i], want[i]) for i in range(c["N"]))
@@ -356,3 +366,18 @@ def test_full_size_first_records(cfgn, n_records):
         assert done >= n_records and worst <= STEP_TOL
     finally:
         sess.close()
+
+
+@pytest.mark.parametrize("cfgn,over", [
+    (1, dict(loss=1, momentum=0.9, K=30)),
+    (2, dict(d=4096 + 4, rows=256, K=24, loss=1, momentum=0.9)),
+    (3, dict(d=1 << 13, rows=1024, K=30, loss=1, momentum=0.9)),
+    (3, dict(d=1 << 13, rows=1024, K=30, loss=1)),
+    (3, dict(d=1 << 13, rows=1024, K=30, momentum=0.5)),
+    (4, dict(d=(1 << 13) + 1, K=40, momentum=0.9)),
+])
+def test_momentum_and_log_loss(cfgn, over):
+    """The optimiser of the paper's own runs (Section 7.2): momentum 0.9 as a per-worker velocity
+    and the log loss, on dense, CSR (dense gradient materialised when a velocity exists) and
+    synthetic gradients, jumps included."""
+    run_parity(inputs.config(cfgn, **over))
