@@ -193,7 +193,9 @@ int hop_set_params(hop_ctx* ctx, const float* p0, int per_worker, int on_device)
 /* Sample count of a worker's data set when no data is attached (host-only contexts): minibatch row
  * ids are drawn modulo this. */
 int hop_set_rows(hop_ctx* ctx, int32_t worker, int64_t rows);
-/* Dense rows-by-d fp32 row-major features and +-1 labels, device memory. */
+/* Dense rows-by-d fp32 row-major features and +-1 labels, device memory.  Attach data before
+ * hop_simulate: the minibatch ids of a schedule are drawn for the row counts known then, and hop_step
+ * returns HOP_ERR_STATE if a worker's row count has changed since. */
 int hop_set_data_dense(hop_ctx* ctx, int32_t worker, const float* X, const float* y, int64_t rows);
 /* CSR features: rowptr int64 [rows+1], col int32 ascending per row, val fp32; labels y; device. */
 int hop_set_data_csr(hop_ctx* ctx, int32_t worker, const int64_t* rowptr, const int32_t* col,
@@ -206,6 +208,7 @@ int hop_set_grad_source(hop_ctx* ctx, int mode, float variance, const float* ext
  * (also when the result is HOP_ERR_DEADLOCK).  Touches no device memory. */
 int hop_simulate(hop_ctx* ctx, const hop_delay_model* delays, int32_t max_iter, hop_schedule** out);
 int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* out);
+/* Frees a schedule and its device-side descriptors; do this before hop_destroy of its context. */
 int hop_schedule_free(hop_schedule* s);
 
 /* Enqueues waves [wave_begin, wave_end) of the schedule: per wave the gradient kernels of its STEP

@@ -80,6 +80,11 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
     const int mode = c->grad_mode;
     const int B = s->batch;
     if ((mode == HOP_GRAD_SVM_DENSE || mode == HOP_GRAD_SVM_CSR) && B <= 0) return HOP_ERR_STATE;
+    // the minibatch ids were drawn modulo the data-set sizes known to hop_simulate: a data set
+    // attached since then must have the same number of rows, or the ids could point past its end
+    if (mode == HOP_GRAD_SVM_DENSE || mode == HOP_GRAD_SVM_CSR)
+        for (int i = 0; i < c->N; ++i)
+            if ((size_t)i >= s->rows_at_sim.size() || s->rows_at_sim[i] != c->data[i].rows) return HOP_ERR_STATE;
     if (B > 0) {
         HOP_HIP(c, hipMalloc((void**)&s->rows_dev, (size_t)R * B * sizeof(int32_t)));
         HOP_HIP(c, hipMemcpy(s->rows_dev, s->batch_rows.data(), (size_t)R * B * sizeof(int32_t),
@@ -487,6 +492,10 @@ int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* v) {
 
 int hop_schedule_free(hop_schedule* s) {
     if (!s) return HOP_ERR_INVALID_ARG;
+    if (s->owner && s->owner->running == s) {
+        s->owner->running = nullptr;
+        s->owner->next_wave = 0;
+    }
     free_device_side(s);
     delete s;
     return HOP_OK;

@@ -65,9 +65,10 @@ struct hop_schedule {
     std::vector<float> src_weight;
     std::vector<int32_t> batch_rows, final_iter, wave_begin, wave_order;
     std::vector<uint64_t> finish_time;
+    std::vector<int64_t> rows_at_sim;   // data-set sizes the minibatch ids were drawn for
 
     // device side, built lazily by hop_step for the context's current gradient mode
-    const hop_ctx* owner = nullptr;
+    hop_ctx* owner = nullptr;
     int built_mode = -1;
     uint64_t built_epoch = 0;
     HopMixJob* mix_dev = nullptr;       // n_records, in wave order

@@ -331,6 +331,8 @@ int hop_run_protocol(const hop_ctx* ctx, const hop_delay_model* dm, int K, hop_s
     bool any_rows = false;
     for (const auto& dd : ctx->data) any_rows = any_rows || dd.rows > 0;
     out->batch = any_rows ? ctx->opts.batch : 0;
+    out->rows_at_sim.clear();
+    for (const auto& dd : ctx->data) out->rows_at_sim.push_back(dd.rows);
     Sim sim{};
     sim.c = ctx;
     sim.dm = dm;

@@ -381,3 +381,23 @@ def test_momentum_and_log_loss(cfgn, over):
     and the log loss, on dense, CSR (dense gradient materialised when a velocity exists) and
     synthetic gradients, jumps included."""
     run_parity(inputs.config(cfgn, **over))
+
+
+def test_data_set_swapped_after_simulate_is_refused():
+    """Minibatch ids are drawn for the row counts known to hop_simulate; a smaller data set attached
+    afterwards must make hop_step fail instead of reading past its end."""
+    c = inputs.config(1, K=3, rows=256)
+    p0, data = make_data(c)
+    sess = Session(c)
+    try:
+        attach(sess, c, p0, data)
+        sess.simulate()
+        sess.step()
+        sess.sync()
+        small = ([x[:100].contiguous() for x in data[0]], [y[:100].contiguous() for y in data[1]])
+        sess.set_dense(*small)
+        with pytest.raises(hop.HopError) as e:
+            sess.step()
+        assert e.value.code == hop.HOP_ERR_STATE
+    finally:
+        sess.close()
