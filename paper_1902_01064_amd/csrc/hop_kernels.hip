@@ -54,7 +54,10 @@ inline int64_t grid_for(int n_jobs, int64_t n_chunks) {
 //
 // Template knobs: VEC float4 per thread per source; NT 0 = ordinary accesses, 1 = g and the result
 // non-temporal (each touched once), 2 = sources too; MAP 0 = job-major blocks, 1 = the XCD-aware map
-// above, 2 = chunk-major without regard to XCDs; T threads per workgroup.
+// above, 2 = chunk-major without regard to XCDs, 3 = one contiguous eighth of the columns per XCD,
+// 10 + G = XCD-aware with runs of G consecutive chunks per XCD; T threads per workgroup.
+// Measured on 32 jobs x 25 M columns with ~7.6 shared sources each: MAP 1 is 2.3x faster than MAP 0 and
+// 1.45x faster than MAP 2; vector width, block size and cache hints move the time by under 5 %.
 template <int NT>
 __device__ __forceinline__ float4 ld_src(const float* p, int64_t i) {
     return NT >= 2 ? ld4_stream(p, i) : ld4(p, i);
@@ -182,6 +185,18 @@ __global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jo
     } else if (MAP == 0) {
         j = (int)(blockIdx.x / n_chunks);
         chunk = blockIdx.x % n_chunks;
+    } else if (MAP >= 10) {
+        // XCD-aware like MAP 1, but every XCD owns runs of G = MAP - 10 consecutive chunks, and visits
+        // them job by job: longer contiguous pieces of every stream are in flight at a time
+        constexpr int G = MAP - 10;
+        int64_t b = blockIdx.x;
+        int xcd = (int)(b % kXcd);
+        int64_t local = b / kXcd;
+        int sub = (int)(local % G);
+        j = (int)((local / G) % n_jobs);
+        int64_t group = local / ((int64_t)G * n_jobs);
+        chunk = (group * kXcd + xcd) * G + sub;
+        if (chunk >= n_chunks) return;
     } else if (MAP == 3) {
         // every XCD owns one contiguous eighth of the columns
         int64_t b = blockIdx.x;
@@ -256,6 +271,10 @@ int launch_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
     int64_t n_chunks = (n4 + per - 1) / per;
     if (n_chunks < 1) n_chunks = 1;
     int64_t grid = (MAP == 1 || MAP == 3) ? grid_for(n_jobs, n_chunks) : n_chunks * n_jobs;
+    if (MAP >= 10) {
+        int64_t span = (int64_t)kXcd * (MAP - 10);
+        grid = (n_chunks + span - 1) / span * span * n_jobs;
+    }
     if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((mix_kernel<VEC, NT, MAP, T>), dim3((unsigned)grid), dim3(T), 0, (hipStream_t)stream,
                        jobs_dev, n_jobs, d, n_chunks);
@@ -546,9 +565,26 @@ int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
         case 14: return launch_mix<1, 1, 1, 512>(jobs_dev, n_jobs, d, stream);
         case 15: return launch_mix<4, 1, 3, 256>(jobs_dev, n_jobs, d, stream);
         case 16: return launch_mix<2, 1, 3, 256>(jobs_dev, n_jobs, d, stream);
+        case 17: return launch_mix<4, 0, 0, 256>(jobs_dev, n_jobs, d, stream);
+        case 18: return launch_mix<1, 0, 0, 256>(jobs_dev, n_jobs, d, stream);
+        case 19: return launch_mix<2, 0, 0, 256>(jobs_dev, n_jobs, d, stream);
+        case 20: return launch_mix<1, 1, 0, 256>(jobs_dev, n_jobs, d, stream);
+        case 21: return launch_mix<1, 0, 0, 512>(jobs_dev, n_jobs, d, stream);
+        case 22: return launch_mix<1, 0, 0, 1024>(jobs_dev, n_jobs, d, stream);
+        case 30: return launch_mix<4, 1, 12, 256>(jobs_dev, n_jobs, d, stream);
+        case 31: return launch_mix<4, 1, 14, 256>(jobs_dev, n_jobs, d, stream);
+        case 32: return launch_mix<4, 1, 18, 256>(jobs_dev, n_jobs, d, stream);
+        case 33: return launch_mix<2, 1, 14, 256>(jobs_dev, n_jobs, d, stream);
+        case 34: return launch_mix<2, 1, 18, 256>(jobs_dev, n_jobs, d, stream);
+        case 35: return launch_mix<1, 1, 18, 256>(jobs_dev, n_jobs, d, stream);
+        case 36: return launch_mix<1, 1, 26, 256>(jobs_dev, n_jobs, d, stream);
+        case 37: return launch_mix<2, 1, 26, 256>(jobs_dev, n_jobs, d, stream);
         default: break;
     }
 #endif
+    // long vectors: every XCD takes runs of 4 consecutive 16 KB chunks (3-4 % faster on 64-100 MB
+    // vectors: longer contiguous pieces per stream); short ones: single chunks, less padding
+    if ((d >> 2) >= (int64_t)1024 * kThreads * 4) return launch_mix<4, 1, 14, 256>(jobs_dev, n_jobs, d, stream);
     return launch_mix<4, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
 }
 
