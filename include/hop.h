@@ -112,7 +112,9 @@ typedef struct {
     uint64_t seed;
     float momentum;               /* mu in [0, 1): v <- mu v + g, x <- reduce - eta v per worker (Section 7.2
                                      uses 0.9); 0 = plain SGD, no velocity buffers */
-    int32_t reserved;
+    uint32_t max_latency;         /* ticks; 0 or 1: every update arrives one tick after its Send, in order;
+                                     larger: seeded uniform 1..max_latency per update, so updates on an edge
+                                     can overtake each other (Section 6.1) and the ring gets s + max_ig + 2 slots */
 } hop_opts;
 
 typedef struct {
@@ -131,6 +133,8 @@ typedef struct {
     int32_t batch;                /* row ids per STEP record, 0 if none */
     int32_t stalled;              /* 1 if the run ended in HOP_ERR_DEADLOCK */
     int32_t n_jumps;
+    int32_t late_sends;           /* updates sent to a receiver already past their tag (Section 6.2 b) */
+    int32_t reserved;
     const int32_t* kind;          /* HOP_STEP / HOP_JUMP */
     const int32_t* worker;
     const int32_t* iter;          /* STEP: the iteration k reduced; JUMP: the iteration jumped to */
@@ -171,7 +175,8 @@ int hop_version(void);
 int hop_opts_default(hop_opts* o);
 
 /* Ring depth D and slot stride (in floats) used for N workers of d parameters under staleness bound
- * s: D = max_ig + 1 for s >= 1 (Section 6.1's #queues), max_ig + 2 for s = 0. */
+ * s: D = max_ig + 1 for s >= 1 (Section 6.1's #queues; s + max_ig + 2 when max_latency > 1),
+ * max_ig + 2 for s = 0. */
 int hop_layout(int64_t d, int32_t s, const hop_opts* o, int32_t* depth, int64_t* stride);
 
 /* Bytes of device memory hop_init needs for rings, gradient buffers and scratch. */

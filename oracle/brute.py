@@ -22,7 +22,8 @@ from collections import deque
 
 
 class Model:
-    def __init__(self, in_nbrs, s, b, K, max_ig=0, skip_on=False, max_skip=10, trigger=1):
+    def __init__(self, in_nbrs, s, b, K, max_ig=0, skip_on=False, max_skip=10, trigger=1, ordered=True):
+        self.ordered = ordered            # False: any update in flight may arrive next (Section 6.1)
         self.n = len(in_nbrs)
         self.inn = [tuple(sorted(l)) for l in in_nbrs]
         outn = [[] for _ in in_nbrs]
@@ -78,7 +79,7 @@ class Model:
                 newest = max(q) if q else -1
                 if max(newest, rcv[e]) >= k - self.s:
                     ok_count += 1
-                if q and newest >= k - self.s:
+                if q and newest >= k - self.s and newest > rcv[e]:
                     acc.append((j, newest))
             elif k in q:
                 ok_count += 1
@@ -101,8 +102,10 @@ class Model:
         it, ph, flight, queue, rcv, tok = state
         mv = []
         for x, e in enumerate(self.edges):
-            if flight[x]:
+            if flight[x] and self.ordered:
                 mv.append(("deliver",) + e)
+            elif flight[x]:
+                mv.extend(("deliver",) + e + (t,) for t in flight[x])
         st = self._thaw(state)
         for i in range(self.n):
             if ph[i] == 0 and self._recv(st, i, it[i])[0]:
@@ -118,8 +121,10 @@ class Model:
         out = []
         if move[0] == "deliver":
             e = self.eidx[(move[1], move[2])]
-            tag = flight[e][0]
-            flight[e] = flight[e][1:]
+            tag = flight[e][0] if len(move) == 3 else move[3]
+            rest = list(flight[e])
+            rest.remove(tag)
+            flight[e] = tuple(rest)
             # staleness mode only ever looks at the newest queued tag
             queue[e] = (max(queue[e] + (tag,)),) if self.s >= 1 else queue[e] + (tag,)
             out.append(("deliver", move[1], move[2], tag))
@@ -194,7 +199,7 @@ class Model:
                 assert want == item, (want, item)
                 continue
             if item[0] == "deliver":
-                mv = ("deliver", item[1], item[2])
+                mv = ("deliver", item[1], item[2]) if self.ordered else ("deliver", item[1], item[2], item[3])
             elif item[0] == "recv":
                 mv = ("fire", item[1])
             elif item[0] == "enter":

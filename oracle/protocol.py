@@ -41,10 +41,19 @@ the repository's design notes):
     block; otherwise advance normally.  The jump's Reduce averages x_{k0+1}
     with what Recv(k0+J-1) accepts, then J tokens move each way.
   - A worker that reaches iteration K still inserts its tokens, sends nothing.
+  - Section 6.1 does not assume that the network keeps messages in order.  With
+    max_latency > 1 every update takes a seeded number of ticks in
+    1..max_latency, so updates on one edge can overtake each other; the queues
+    are multisets of tags, so nothing else changes.  Section 6.2 (b) (do not
+    send what the receiver is already past) is kept as a counter, late_sends:
+    in exact-tag mode such an update is always dropped at the next dequeue.
 
 Versions live in a ring of D slots per worker, slot = version mod D, with
 D = max_ig + 1 in staleness mode (the paper's #queues) and max_ig + 2 in
-exact-tag mode (the ring also holds the not yet sent x_{k+1}).
+exact-tag mode (the ring also holds the not yet sent x_{k+1}).  With
+out-of-order delivery a reader in iteration k may take a tag as old as k - s
+while the sender, at most max_ig iterations ahead, has already produced version
+k + max_ig + 1: staleness mode then needs D = s + max_ig + 2.
 """
 import heapq
 from collections import deque
@@ -100,8 +109,10 @@ def shortest_paths(out_nbrs):
     return dist
 
 
-def ring_depth(s, max_ig):
-    return max_ig + 1 if s >= 1 else max_ig + 2
+def ring_depth(s, max_ig, max_latency=1):
+    if s >= 1:
+        return max_ig + 1 if max_latency <= 1 else s + max_ig + 2
+    return max_ig + 2
 
 
 class Record:
@@ -119,7 +130,7 @@ class Hop:
 
     def __init__(self, in_nbrs, W, s, b, K, max_ig=0, skip_on=False, max_skip=10,
                  trigger=1, seed=0, delay_kind=rng.DELAY_NONE, mult=None,
-                 table=None, check=True, trace=False):
+                 table=None, check=True, trace=False, max_latency=1):
         self.N = len(in_nbrs)
         self.in_nbrs = [sorted(l) for l in in_nbrs]
         self.out_nbrs = transpose(self.in_nbrs)
@@ -130,7 +141,8 @@ class Hop:
         self.seed, self.delay_kind = int(seed), int(delay_kind)
         self.mult = [1.0] * self.N if mult is None else [float(m) for m in mult]
         self.table = table
-        self.D = ring_depth(self.s, self.max_ig)
+        self.max_latency = int(max_latency)
+        self.D = ring_depth(self.s, self.max_ig, self.max_latency)
         self.check = check
         for i in range(self.N):
             if self.b > 0 and self.b >= len(self.in_nbrs[i]):
@@ -154,7 +166,9 @@ class Hop:
                     seen = new
                 if seen >= k - s:
                     satisfied += 1
-                if new is not None and new >= k - s:
+                # an update no newer than one already reduced carries nothing new (it can only
+                # show up after a newer one when the network reorders)
+                if new is not None and new >= k - s and new > self.iter_rcv[(j, i)]:
                     accepted.append((j, new))
             else:
                 if k in q:
@@ -199,7 +213,10 @@ class Hop:
             self.finish_time[i] = T
         else:
             for j in self.out_nbrs[i]:
-                heapq.heappush(self.events, (T + LAT, EV_ARRIVE, j, i, k))
+                lat = rng.latency_ticks(self.seed, self.max_latency, i, j, k)
+                heapq.heappush(self.events, (T + lat, EV_ARRIVE, j, i, k))
+                if self.Iter[j] > k:
+                    self.late_sends += 1
             dur = rng.duration_ticks(self.seed, self.delay_kind, self.N, self.mult[i], i, k,
                                      self.table)
             if dur < rng.TICKS_NEVER:
@@ -290,6 +307,7 @@ class Hop:
         self.iter_rcv = {(j, i): -1 for i in range(N) for j in self.in_nbrs[i]}
         self.tokens = {(i, j): self.max_ig - 1 for i in range(N) for j in self.in_nbrs[i]}
         self.n_jumps = 0
+        self.late_sends = 0
         self.max_gap = 0
         self.max_queue = 0
         for i in range(N):

@@ -24,6 +24,7 @@ M64 = (1 << 64) - 1
 STREAM_DELAY = 1
 STREAM_BATCH = 2
 STREAM_SYNTHGRAD = 6
+STREAM_LATENCY = 7
 
 TICKS_PER_UNIT = 1 << 20          # one time unit of simulated Compute
 TICKS_NEVER = 1 << 62             # a duration at or above this never completes
@@ -73,6 +74,14 @@ def duration_ticks(seed, kind, n_workers, mult_i, i, k, table=None):
     if t >= float(TICKS_NEVER):
         return TICKS_NEVER
     return max(1, int(math.floor(t)))
+
+
+def latency_ticks(seed, max_latency, sender, receiver, tag):
+    """Ticks an update needs from Send to the receiver's queue: 1, or uniform in 1..max_latency
+    keyed by (sender, receiver, tag) - later updates can then overtake earlier ones."""
+    if max_latency <= 1:
+        return 1
+    return 1 + mix(seed, STREAM_LATENCY, sender, receiver, tag) % max_latency
 
 
 def batch_rows(seed, i, k, batch, rows):

@@ -24,6 +24,15 @@ int effective_max_ig(int s, const hop_opts* o) {
     return ig > 0 ? ig : std::max(s, 1);
 }
 
+// Versions a ring must hold: the paper's #queues = max_ig + 1 when updates arrive in order (the tag
+// taken is the sender's last Send); with reordering a reader in iteration k may take tag k - s while
+// the sender, at most max_ig ahead, has produced version k + max_ig + 1.  Exact-tag mode (s = 0) reads
+// tag k while versions up to k + max_ig + 1 exist.
+int ring_depth(int s, int max_ig, uint32_t max_latency) {
+    if (s >= 1) return max_latency > 1 ? s + max_ig + 2 : max_ig + 1;
+    return max_ig + 2;
+}
+
 // Every slot starts on a 256-byte boundary; the extra 256 bytes keep the slots of a power-of-two d
 // from all mapping to the same HBM channel phase.
 int64_t slot_stride(int64_t d) {
@@ -263,13 +272,14 @@ int hop_opts_default(hop_opts* o) {
     o->loss = HOP_LOSS_HINGE;
     o->seed = 0;
     o->momentum = 0.f;
+    o->max_latency = 0;
     return HOP_OK;
 }
 
 int hop_layout(int64_t d, int32_t s, const hop_opts* o, int32_t* depth, int64_t* stride) {
     if (d < 1 || s < 0) return HOP_ERR_INVALID_ARG;
     int ig = effective_max_ig(s, o);
-    if (depth) *depth = s >= 1 ? ig + 1 : ig + 2;
+    if (depth) *depth = ring_depth(s, ig, o ? o->max_latency : 0);
     if (stride) *stride = slot_stride(d);
     return HOP_OK;
 }
@@ -301,7 +311,7 @@ int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64
     if (!c) return HOP_ERR_NOMEM;
     c->N = N; c->d = d; c->s = s; c->b = b; c->opts = o;
     c->max_ig = effective_max_ig(s, &o);
-    c->D = s >= 1 ? c->max_ig + 1 : c->max_ig + 2;
+    c->D = ring_depth(s, c->max_ig, o.max_latency);
     c->stride = slot_stride(d);
     int rc = HOP_OK;
     c->in_nbrs.assign(N, {});
@@ -471,6 +481,7 @@ int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* v) {
     v->batch = s->batch;
     v->stalled = s->stalled;
     v->n_jumps = s->n_jumps;
+    v->late_sends = s->late_sends;
     v->kind = s->kind.data();
     v->worker = s->worker.data();
     v->iter = s->iter.data();

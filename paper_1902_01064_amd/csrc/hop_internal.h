@@ -51,7 +51,7 @@ int hopk_dense_nseg(int64_t d);                 // column segments per row in th
 
 // ---- host-side random numbers (hop_sim.cpp) ---------------------------------------
 namespace hoprng {
-enum : uint64_t { STREAM_DELAY = 1, STREAM_BATCH = 2, STREAM_SYNTHGRAD = 6 };
+enum : uint64_t { STREAM_DELAY = 1, STREAM_BATCH = 2, STREAM_SYNTHGRAD = 6, STREAM_LATENCY = 7 };
 uint64_t mix(uint64_t seed, uint64_t stream, uint64_t a, uint64_t b, uint64_t c);
 void synth_keys(uint64_t seed, int worker, int iter, uint32_t* k0, uint32_t* k1, uint32_t* k2);
 float synth_scale(float variance);
@@ -59,7 +59,7 @@ float synth_scale(float variance);
 
 // ---- schedule ----------------------------------------------------------------------
 struct hop_schedule {
-    int N = 0, D = 0, K = 0, batch = 0, stalled = 0, n_jumps = 0, n_waves = 0;
+    int N = 0, D = 0, K = 0, batch = 0, stalled = 0, n_jumps = 0, n_waves = 0, late_sends = 0;
     std::vector<int32_t> kind, worker, iter, wave, out_slot, src_begin, src_worker, src_tag, src_slot;
     std::vector<uint64_t> time;
     std::vector<float> src_weight;

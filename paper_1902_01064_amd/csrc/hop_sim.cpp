@@ -102,6 +102,15 @@ struct Sim {
         return f < 1.0 ? 1ull : (uint64_t)f;
     }
 
+    // Ticks from Send to the receiver's queue: 1, or seeded uniform in 1..max_latency (Section 6.1
+    // does not assume that the network keeps the order of messages).
+    uint64_t latency(int sender, int receiver, int tag) const {
+        const uint64_t ml = c->opts.max_latency;
+        if (ml <= 1) return LAT;
+        return 1 + hoprng::mix(c->opts.seed, hoprng::STREAM_LATENCY, (uint64_t)sender, (uint64_t)receiver,
+                               (uint64_t)tag) % ml;
+    }
+
     // Recv(k) at worker i on a snapshot of its queues: can it complete, and what does it take?
     bool recv_eval(int i, int k, std::vector<std::pair<int, int>>& acc) const {
         acc.clear();
@@ -116,7 +125,9 @@ struct Sim {
                 for (int t : q) newest = std::max(newest, t);
                 int seen = std::max(iter_rcv[e], any ? newest : -1);
                 if (seen >= k - s) ++satisfied;
-                if (any && newest >= k - s) acc.emplace_back(nb[p], newest);
+                // an update no newer than one already reduced carries nothing new (possible only
+                // when the network reorders)
+                if (any && newest >= k - s && newest > iter_rcv[e]) acc.emplace_back(nb[p], newest);
             } else {
                 if (std::find(q.begin(), q.end(), k) != q.end()) {
                     ++satisfied;
@@ -200,7 +211,10 @@ struct Sim {
             state[i] = FINISHED;
             out->finish_time[i] = T;
         } else {
-            for (int j : c->out_nbrs[i]) events.push(Event{T + LAT, EV_ARRIVE, j, i, k});
+            for (int j : c->out_nbrs[i]) {
+                events.push(Event{T + latency(i, j, k), EV_ARRIVE, j, i, k});
+                if (iter[j] > k) out->late_sends += 1;     // Section 6.2 (b): the receiver is already past it
+            }
             uint64_t dur = duration(i, k);
             if (dur < HOP_TICKS_NEVER) events.push(Event{T + dur, EV_DONE, i, 0, k});
             state[i] = COMPUTING;

@@ -51,7 +51,7 @@ class hop_opts(C.Structure):
     _fields_ = [("max_ig", C.c_int32), ("skip_on", C.c_int32), ("max_skip", C.c_int32),
                 ("trigger", C.c_int32), ("lr", C.c_float), ("lambda_", C.c_float),
                 ("batch", C.c_int32), ("loss", C.c_int32), ("seed", C.c_uint64),
-                ("momentum", C.c_float), ("reserved", C.c_int32)]
+                ("momentum", C.c_float), ("max_latency", C.c_uint32)]
 
 
 class hop_delay_model(C.Structure):
@@ -65,7 +65,8 @@ _I32P, _U64P, _F32P = C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.POINTER(C.c
 class hop_schedule_arrays(C.Structure):
     _fields_ = [("n_records", C.c_int32), ("n_sources", C.c_int32), ("n_waves", C.c_int32),
                 ("n_workers", C.c_int32), ("depth", C.c_int32), ("batch", C.c_int32),
-                ("stalled", C.c_int32), ("n_jumps", C.c_int32),
+                ("stalled", C.c_int32), ("n_jumps", C.c_int32), ("late_sends", C.c_int32),
+                ("reserved", C.c_int32),
                 ("kind", _I32P), ("worker", _I32P), ("iter", _I32P), ("time", _U64P), ("wave", _I32P),
                 ("out_slot", _I32P), ("src_begin", _I32P), ("src_worker", _I32P), ("src_tag", _I32P),
                 ("src_slot", _I32P), ("src_weight", _F32P), ("batch_rows", _I32P),
@@ -154,12 +155,12 @@ def _np_i32(a):
 
 
 def make_opts(max_ig=0, skip_on=False, max_skip=10, trigger=1, lr=0.01, lam=1e-4, batch=0, seed=0,
-              loss=HOP_LOSS_HINGE, momentum=0.0):
+              loss=HOP_LOSS_HINGE, momentum=0.0, max_latency=0):
     o = hop_opts()
     _check(load().hop_opts_default(C.byref(o)), "hop_opts_default")
     o.max_ig, o.skip_on, o.max_skip, o.trigger = int(max_ig), int(bool(skip_on)), int(max_skip), int(trigger)
     o.lr, o.lambda_, o.batch, o.seed = float(lr), float(lam), int(batch), int(seed)
-    o.loss, o.momentum = int(loss), float(momentum)
+    o.loss, o.momentum, o.max_latency = int(loss), float(momentum), int(max_latency)
     return o
 
 
@@ -235,6 +236,7 @@ class Schedule:
         R, S, Wv, N = v.n_records, v.n_sources, v.n_waves, v.n_workers
         self.n_records, self.n_sources, self.n_waves, self.n_workers = R, S, Wv, N
         self.depth, self.batch, self.stalled, self.n_jumps = v.depth, v.batch, bool(v.stalled), v.n_jumps
+        self.late_sends = v.late_sends
 
         def arr(p, n, dt):
             if n == 0 or not p:

@@ -28,7 +28,8 @@ LOSS = {0: "hinge", 1: "log"}
 def oracle_schedule(c, K):
     h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], K, max_ig=c["max_ig"], skip_on=c["skip_on"],
                      max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
-                     delay_kind=c["delay_kind"], mult=c["mult"], check=False)
+                     delay_kind=c["delay_kind"], mult=c["mult"], check=False,
+                     max_latency=c.get("max_latency", 1))
     recs = h.run()
     return h, recs
 
@@ -401,3 +402,12 @@ def test_data_set_swapped_after_simulate_is_refused():
         assert e.value.code == hop.HOP_ERR_STATE
     finally:
         sess.close()
+
+
+@pytest.mark.parametrize("cfgn,over", [(3, dict(d=1 << 13, rows=1024, K=30, max_latency=3 << 19)),
+                                       (4, dict(d=(1 << 13) + 2, K=40, max_latency=1 << 20)),
+                                       (2, dict(d=2048, rows=256, K=30, max_latency=1 << 21))])
+def test_out_of_order_delivery(cfgn, over):
+    """Updates that overtake each other on an edge (Section 6.1): deeper rings (s + max_ig + 2 slots),
+    same parity bars."""
+    run_parity(inputs.config(cfgn, **over))

@@ -34,7 +34,8 @@ def test_library_exports_every_declared_symbol():
 def host_ctx(c, **over):
     row_ptr, col = inputs.to_csr(c["in_nbrs"])
     o = hop.make_opts(max_ig=c["max_ig"], skip_on=c["skip_on"], max_skip=c["max_skip"],
-                      trigger=c["trigger"], lr=c["lr"], lam=c["lam"], batch=c["batch"], seed=c["seed"])
+                      trigger=c["trigger"], lr=c["lr"], lam=c["lam"], batch=c["batch"], seed=c["seed"],
+                      max_latency=c.get("max_latency", 0))
     ctx = hop.hop_init(row_ptr, col, c["W"], c["N"], c["d"], c["s"], c["b"], o)
     for i in range(c["N"]):
         if c["batch"]:
@@ -45,13 +46,14 @@ def host_ctx(c, **over):
 def oracle_run(c, K):
     h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], K, max_ig=c["max_ig"], skip_on=c["skip_on"],
                      max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
-                     delay_kind=c["delay_kind"], mult=c["mult"], check=False)
+                     delay_kind=c["delay_kind"], mult=c["mult"], check=False,
+                     max_latency=c.get("max_latency", 1))
     return h, h.run()
 
 
 def assert_same_schedule(c, sched, h, recs, K):
     assert sched.n_records == len(recs) and sched.depth == h.D
-    assert sched.stalled == h.stalled and sched.n_jumps == h.n_jumps
+    assert sched.stalled == h.stalled and sched.n_jumps == h.n_jumps and sched.late_sends == h.late_sends
     assert list(sched.kind) == [r.kind for r in recs]
     assert list(sched.worker) == [r.worker for r in recs]
     assert list(sched.iter) == [r.k for r in recs]
