@@ -1,0 +1,25 @@
+"""The library's host simulator under AddressSanitizer and UBSan (host code only, no GPU): built with g++
+together with a small driver that walks a grid of graphs, modes, frozen workers and latencies."""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="needs g++")
+def test_simulator_is_clean_under_asan_and_ubsan(tmp_path):
+    exe = str(tmp_path / "sim_driver")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
+           "-ffp-contract=off", "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(ROOT, "paper_1902_01064_amd", "csrc"),
+           os.path.join(ROOT, "tests", "sim_driver.cpp"),
+           os.path.join(ROOT, "paper_1902_01064_amd", "csrc", "hop_sim.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0:verify_asan_link_order=0")
+    out = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-4000:]
+    assert out.stdout.startswith("ok runs=")
+    assert int(out.stdout.split("runs=")[1].split()[0]) > 200
