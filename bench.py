@@ -7,8 +7,9 @@ hop_step (gradient kernels + fused Reduce/Apply) for all iterations of all worke
 default workload is config 4 of the synthetic suite: 32 workers on a ring with chords,
 Metropolis weights, staleness 4, one backup worker, two 3x stragglers with skipping,
 d = 25 000 000 fp32 parameters per replica, synthetic gradients, 100 iterations.
-Inputs (initial replicas, schedule, job descriptors) are resident in HBM before the
-timed region.  Prints ONE JSON line.
+Inputs (initial replicas, data, schedule, job descriptors) are resident in HBM before the
+timed region.  Prints ONE JSON line; the other four configs of the suite are run briefly
+afterwards and reported under "other_configs" (not part of value).
 """
 import argparse
 import json
@@ -21,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+METRIC = "worker-updates/sec and mixing-kernel HBM GB/s (% of peak) at N workers, d params"
 
 
 def read_traffic(name):
@@ -71,6 +73,75 @@ def cpu_baseline(c, recs, p0, budget_s=20.0):
                       % (done, c["d"], dt)}
 
 
+def run_config(cfgn, steps, warmup, graph, over=None):
+    """Sets one workload up on cuda:0, times `steps` passes, returns (result dict, config, p0)."""
+    import torch
+
+    from paper_1902_01064_amd import hop, inputs
+    from paper_1902_01064_amd.session import Session, make_data
+
+    c = inputs.config(cfgn, **(over or {}))
+    dev = "cuda:0"
+    sess = Session(c, dev)
+    try:
+        p0, data = make_data(c, dev)
+        if c["model"] == "dense":
+            sess.set_dense(*data)
+        elif c["model"] == "csr":
+            sess.set_csr(data)
+        else:
+            hop.hop_set_grad_source(sess.ctx, hop.HOP_GRAD_SYNTH, c["grad_var"])
+        sess.set_params(p0)
+        sched = sess.simulate()
+        n_step = int((sched.kind == hop.HOP_STEP).sum())
+        n_jump = int((sched.kind == hop.HOP_JUMP).sum())
+        A = (sched.src_begin[1:] - sched.src_begin[:-1])
+        if graph:
+            hop.hop_use_graph(sess.ctx, 1)
+        for _ in range(warmup):
+            sess.step()
+        sess.sync()
+        if not graph:
+            hop.hop_profile(sess.ctx, 1)     # HIP events around every kernel group, inside the timed region
+        sess.sync()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            sess.step()
+        sess.sync()
+        t1 = time.perf_counter()
+        if graph:                            # graph replays cannot be timed per kernel: one extra pass
+            hop.hop_profile(sess.ctx, 1)
+            sess.step()
+            sess.sync()
+        mix_ms, mix_n, mix_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_MIX)
+        grad_ms, grad_n, grad_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_GRAD)
+        syn_ms, syn_n, syn_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_SYNTH)
+        hop.hop_profile(sess.ctx, 0)
+        elapsed = t1 - t0
+
+        def rate(b, ms):
+            return b / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        res = {
+            "value": n_step * steps / elapsed,
+            "ms_per_step": elapsed * 1e3 / steps,
+            "config": {
+                "workload": c["name"] + (" (config %d of the synthetic suite)" % cfgn),
+                "N": c["N"], "d": c["d"], "s": c["s"], "b": c["b"], "iterations": c["K"],
+                "step_records": n_step, "jump_records": n_jump, "waves": int(sched.n_waves),
+                "mean_A": float(A.mean()), "max_A": int(A.max()),
+                "step_definition": "one pass of hop_step over the whole schedule",
+                "launch": "hip graph replay" if graph else "kernel by kernel",
+            },
+            "mix": {"ms": mix_ms, "launches": int(mix_n), "bytes": mix_bytes, "GBps": rate(mix_bytes, mix_ms)},
+            "grad": {"ms": grad_ms, "launches": int(grad_n), "GBps": rate(grad_bytes, grad_ms)},
+            "synth": {"ms": syn_ms, "launches": int(syn_n), "GBps": rate(syn_bytes, syn_ms)},
+        }
+        return res, c, p0
+    finally:
+        sess.close()
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +150,7 @@ def main():
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--d", type=int, default=0, help="override the parameter count (not a valid bench line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the brief runs of the other configs")
     ap.add_argument("--graph", action="store_true",
                     help="time HIP-graph replays of the pass (kernel figures then come from one extra, "
                          "untimed kernel-by-kernel pass)")
@@ -101,99 +173,52 @@ def main():
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
-    import torch
-
-    from oracle import protocol
-    from paper_1902_01064_amd import hop, inputs
-    from paper_1902_01064_amd.session import Session, make_data
-
-    over = {"d": args.d} if args.d else {}
-    c = inputs.config(args.config, **over)
-    dev = "cuda:0"
-    sess = Session(c, dev)
-    p0, data = make_data(c, dev)
-    if c["model"] == "dense":
-        sess.set_dense(*data)
-    elif c["model"] == "csr":
-        sess.set_csr(data)
-    else:
-        hop.hop_set_grad_source(sess.ctx, hop.HOP_GRAD_SYNTH, c["grad_var"])
-    sess.set_params(p0)
-    sched = sess.simulate()
-    n_step = int((sched.kind == hop.HOP_STEP).sum())
-    n_jump = int((sched.kind == hop.HOP_JUMP).sum())
-    A = (sched.src_begin[1:] - sched.src_begin[:-1])
-
-    if args.graph:
-        hop.hop_use_graph(sess.ctx, 1)
-    for _ in range(args.warmup):
-        sess.step()
-    sess.sync()
-    if not args.graph:
-        hop.hop_profile(sess.ctx, 1)
-    sess.sync()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        sess.step()
-    sess.sync()
-    t1 = time.perf_counter()
-    if args.graph:
-        hop.hop_profile(sess.ctx, 1)
-        sess.step()
-        sess.sync()
-    mix_ms, mix_n, mix_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_MIX)
-    grad_ms, grad_n, grad_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_GRAD)
-    syn_ms, syn_n, syn_bytes = hop.hop_profile_read(sess.ctx, hop.HOP_KERNEL_SYNTH)
-    hop.hop_profile(sess.ctx, 0)
-
-    elapsed = t1 - t0
-    achieved = mix_bytes / (mix_ms * 1e-3) / 1e9 if mix_ms > 0 else 0.0
+    res, c, p0 = run_config(args.config, args.steps, args.warmup, args.graph, {"d": args.d} if args.d else None)
+    mix = res["mix"]
     out = {
-        "metric": "worker-updates/sec and mixing-kernel HBM GB/s (% of peak) at N workers, d params",
-        "value": n_step * args.steps / elapsed,
+        "metric": METRIC,
+        "value": res["value"],
         "unit": "worker-updates/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": elapsed * 1e3 / args.steps,
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {
-            "workload": c["name"] + (" (config %d of the synthetic suite)" % args.config),
-            "N": c["N"], "d": c["d"], "s": c["s"], "b": c["b"], "iterations": c["K"],
-            "step_records": n_step, "jump_records": n_jump, "waves": int(sched.n_waves),
-            "mean_A": float(A.mean()), "max_A": int(A.max()),
-            "step_definition": "one pass of hop_step over the whole schedule",
-            "launch": "hip graph replay" if args.graph else "kernel by kernel",
-        },
+        "config": res["config"],
         "roofline": {
-            "bound": "hbm", "kernel": "mix_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
+            "bound": "hbm", "kernel": "mix_kernel", "achieved": mix["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": mix["GBps"] / HBM_PEAK_GBS,
             "traffic": read_traffic("hop_mix_cfg%d_traffic.txt" % args.config),
-            "launches": int(mix_n), "avg_launch_us": mix_ms * 1e3 / max(mix_n, 1),
-            "algorithmic_bytes_per_launch": mix_bytes / max(mix_n, 1),
+            "launches": mix["launches"], "avg_launch_us": mix["ms"] * 1e3 / max(mix["launches"], 1),
+            "algorithmic_bytes_per_launch": mix["bytes"] / max(mix["launches"], 1),
         },
-        "kernels": {
-            "mix": {"ms": mix_ms, "launches": int(mix_n), "GBps": achieved},
-            "grad": {"ms": grad_ms, "launches": int(grad_n),
-                     "GBps": grad_bytes / (grad_ms * 1e-3) / 1e9 if grad_ms > 0 else 0.0},
-            "synth": {"ms": syn_ms, "launches": int(syn_n),
-                      "GBps": syn_bytes / (syn_ms * 1e-3) / 1e9 if syn_ms > 0 else 0.0},
-        },
+        "kernels": {k: {kk: vv for kk, vv in res[k].items() if kk != "bytes"} for k in ("mix", "grad", "synth")},
     }
     if not args.no_cpu_baseline:
-        h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], c["K"], max_ig=c["max_ig"],
-                         skip_on=c["skip_on"], max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
-                         delay_kind=c["delay_kind"], mult=c["mult"], check=False)
-        recs = h.run()
+        from oracle import protocol
         if c["model"] == "synth":
-            out["cpu_baseline"] = cpu_baseline(c, recs, p0)
+            h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], c["K"], max_ig=c["max_ig"],
+                             skip_on=c["skip_on"], max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
+                             delay_kind=c["delay_kind"], mult=c["mult"], check=False)
+            out["cpu_baseline"] = cpu_baseline(c, h.run(), p0)
         else:
             out["cpu_baseline"] = None
-    sess.close()
+    del p0
+    if not args.no_others and not args.d:
+        others = {}
+        for n in (1, 2, 3, 5):
+            if n == args.config:
+                continue
+            r, _, _ = run_config(n, 2, 1, True)
+            others[r["config"]["workload"]] = {
+                "worker_updates_per_s": r["value"], "ms_per_step": r["ms_per_step"], "launch": r["config"]["launch"],
+                "records": r["config"]["step_records"] + r["config"]["jump_records"], "waves": r["config"]["waves"],
+                "mix_GBps": r["mix"]["GBps"], "grad_GBps": r["grad"]["GBps"]}
+        out["other_configs"] = others
     print(json.dumps(out))
 
 
