@@ -261,7 +261,7 @@ int hop_svm_grad_dense(const float* X, const float* y, const float* w, const int
 int hop_svm_grad_csr(const int64_t* rowptr, const int32_t* col, const float* val, const float* y,
                      const float* w, const int32_t* rows_dev, int32_t B, int64_t d, float lambda,
                      int32_t loss, float* g, float* coef, void* hip_stream);
-/* Synthetic gradient of (seed, worker, iteration): centred sum of 12 hashed bytes per element times
+/* Synthetic gradient of (seed, worker, iteration): centred sum of 12 pairwise independent hashed bytes per element times
  * sqrt(variance / 65535). */
 int hop_synth_grad(uint64_t seed, int32_t worker, int32_t iter, float variance, float* g, int64_t d,
                    void* hip_stream);

@@ -124,15 +124,20 @@ def synth_keys(seed, i, k):
 def synth_grad(seed, i, k, cols, variance):
     """Synthetic gradient of (worker i, iteration k) at the given columns.
 
-    Each element is a centred sum of 12 hashed bytes (an Irwin-Hall
-    approximation of a normal draw) times one fp32 scale: integer work plus a
-    single correctly rounded multiply, so every implementation agrees bit for
-    bit.  Returns float32.
+    Each element is a centred sum of 12 bytes (an Irwin-Hall approximation of
+    a normal draw) times one fp32 scale: the bytes of two hashed words a, b of
+    the column index and of (a + rotl(b, 16)) ^ k2, which is uniform and
+    independent of a and of b taken singly, so the bytes are pairwise
+    independent and the variance is exactly 12 (256^2 - 1) / 12.  Integer work
+    plus a single correctly rounded multiply: every implementation agrees bit
+    for bit.  Returns float32.
     """
     cols = np.asarray(cols, dtype=np.int64)
     c32 = (cols & 0xFFFFFFFF).astype(np.uint32)
     k0, k1, k2 = synth_keys(seed, i, k)
-    s = (_byte_sum(_h32(c32 ^ np.uint32(k0))) + _byte_sum(_h32(c32 ^ np.uint32(k1)))
-         + _byte_sum(_h32(c32 ^ np.uint32(k2))))
+    a = _h32(c32 ^ np.uint32(k0))
+    b = _h32(c32 ^ np.uint32(k1))
+    t = (a + ((b << np.uint32(16)) | (b >> np.uint32(16)))) ^ np.uint32(k2)   # wraps modulo 2^32
+    s = _byte_sum(a) + _byte_sum(b) + _byte_sum(t)
     centred = (s - SYNTH_MEAN).astype(np.float32)
     return centred * synth_scale(variance)

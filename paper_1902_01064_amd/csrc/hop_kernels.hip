@@ -282,7 +282,7 @@ int launch_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
 }
 
 // ------------------------------------------------------------------- synthetic gradient ----
-// g[c] = (sum of the 12 bytes of h32(c ^ k0), h32(c ^ k1), h32(c ^ k2) - 1530) * scale:
+// g[c] = (sum of the 12 bytes of a = h32(c ^ k0), b = h32(c ^ k1), (a + rotl(b, 16)) ^ k2  - 1530) * scale:
 // integer work and one correctly rounded multiply, so any implementation agrees bit for bit.
 __device__ __forceinline__ uint32_t h32(uint32_t x) {
     x ^= x >> 16;
@@ -296,9 +296,14 @@ __device__ __forceinline__ uint32_t byte_sum(uint32_t x, uint32_t acc) {
     return __builtin_amdgcn_sad_u8(x, 0u, acc);       // acc + sum of the four bytes of x
 }
 __device__ __forceinline__ float synth_one(uint32_t c, uint32_t k0, uint32_t k1, uint32_t k2, float scale) {
-    uint32_t s = byte_sum(h32(c ^ k0), 0u);
-    s = byte_sum(h32(c ^ k1), s);
-    s = byte_sum(h32(c ^ k2), s);
+    // two hashed words and a third made of both: a + rotl(b, 16) is uniform and independent of a and of
+    // b taken one at a time, so the twelve bytes are pairwise independent and the variance is exact,
+    // at two thirds of the integer multiplies (32-bit multiplies are the slow instruction here)
+    const uint32_t a = h32(c ^ k0), b = h32(c ^ k1);
+    const uint32_t t = (a + ((b << 16) | (b >> 16))) ^ k2;
+    uint32_t s = byte_sum(a, 0u);
+    s = byte_sum(b, s);
+    s = byte_sum(t, s);
     return (float)((int)s - 1530) * scale;
 }
 
