@@ -235,8 +235,9 @@ int hop_use_graph(hop_ctx* ctx, int enable);
 int hop_params(hop_ctx* ctx, int32_t worker, const float** dev_ptr, int32_t* iter);
 /* Address of one ring slot (device, d floats). */
 int hop_slot(hop_ctx* ctx, int32_t worker, int32_t slot, float** dev_ptr);
-/* Hinge coefficients c_m = y_m / B (active) or 0 of a STEP record as the gradient kernel computed
- * them (device, batch floats); valid after that record's wave has run. */
+/* Loss coefficients c_m of a STEP record (hinge: y_m / B where active, else 0; log loss: see
+ * hop_svm_grad_dense) as the gradient kernel computed them (device, batch floats); valid after that
+ * record's wave has run and until the schedule is freed or its descriptors are rebuilt. */
 int hop_coef(hop_ctx* ctx, const hop_schedule* s, int32_t record, const float** dev_ptr);
 
 /* Per-kernel timing with HIP events on the context's stream.  hop_profile_read synchronises the
@@ -246,7 +247,11 @@ int hop_coef(hop_ctx* ctx, const hop_schedule* s, int32_t record, const float** 
 int hop_profile(hop_ctx* ctx, int enable);
 int hop_profile_read(hop_ctx* ctx, int kernel, double* ms, int64_t* launches, double* bytes);
 
-/* Stand-alone kernels on caller-supplied device memory (same code the schedule runs). */
+/* Stand-alone kernels on caller-supplied device memory (same code the schedule runs).  Unlike
+ * hop_step these calls are synchronous: they upload a small descriptor (hipMalloc / hipFree inside),
+ * launch on the given stream and wait for it.  All vectors must be 16-byte aligned (when d is a
+ * multiple of 4 this includes every row of X); a misaligned or NULL pointer, A outside 1..HOP_MAX_A
+ * or B outside 1..1024 gives HOP_ERR_INVALID_ARG and nothing is launched. */
 /* Fused Reduce + Apply for n_jobs independent jobs (host array), each over d columns. */
 int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* hip_stream);
 /* Linear-SVM minibatch (sub)gradient g = lambda w - sum_m c_m x_{r_m}; hinge: c_m = y/B if
