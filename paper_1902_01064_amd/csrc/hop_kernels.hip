@@ -508,19 +508,43 @@ __global__ __launch_bounds__(kThreads) void csr_margin_kernel(const HopGradJob* 
 }
 
 // target[col] += factor * c_m * val for the active rows (the sparse part of -eta g, or of g).
-__global__ __launch_bounds__(kThreads) void csr_scatter_kernel(const HopGradJob* __restrict__ jobs, int B,
-                                                               int rows_per_job_blocks, float factor) {
+// One wavefront per minibatch row, 16 rows per workgroup, all in flight together.  Sparse features
+// are heavy-tailed (a few columns occur in almost every row) and fp32 atomics on one address
+// serialise in L2: B atomics in a chain on the hottest column would set the kernel's duration.
+// Contributions to the first kHotCols columns are therefore added up in LDS first and leave the
+// workgroup as one global atomic per column touched (16 times fewer on the hot ones).
+constexpr int kScatterThreads = 1024;
+constexpr int kScatterRows = kScatterThreads / 64;
+constexpr int kHotCols = 1024;
+
+__global__ __launch_bounds__(kScatterThreads) void csr_scatter_kernel(const HopGradJob* __restrict__ jobs, int B,
+                                                                      int blocks_per_job, float factor) {
+    __shared__ float hot[kHotCols];
     const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const HopGradJob* job = jobs + blockIdx.x / rows_per_job_blocks;
-    const int m = (blockIdx.x % rows_per_job_blocks) * (kThreads / 64) + wv;
-    if (m >= B) return;
-    const float c = job->coef[m];
-    if (c == 0.f) return;
-    const int r = job->rows[m];
-    const int64_t lo = job->rowptr[r], hi = job->rowptr[r + 1];
+    const HopGradJob* job = jobs + blockIdx.x / blocks_per_job;
+    const int m = (blockIdx.x % blocks_per_job) * kScatterRows + wv;
+    for (int i = threadIdx.x; i < kHotCols; i += kScatterThreads) hot[i] = 0.f;
+    __syncthreads();
     float* target = job->out;
-    const float f = factor * c;
-    for (int64_t p = lo + lane; p < hi; p += 64) unsafeAtomicAdd(target + job->col[p], f * job->val[p]);
+    if (m < B) {
+        const float c = job->coef[m];
+        if (c != 0.f) {
+            const int r = job->rows[m];
+            const int64_t lo = job->rowptr[r], hi = job->rowptr[r + 1];
+            const float f = factor * c;
+            for (int64_t p = lo + lane; p < hi; p += 64) {
+                const int col = job->col[p];
+                const float v = f * job->val[p];
+                if (col < kHotCols) atomicAdd(&hot[col], v);
+                else unsafeAtomicAdd(target + col, v);
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kHotCols; i += kScatterThreads) {
+        const float v = hot[i];
+        if (v != 0.f) unsafeAtomicAdd(target + i, v);
+    }
 }
 
 // g = lambda w, the dense part of a CSR gradient when a dense g is wanted.
@@ -643,9 +667,9 @@ int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, voi
 
 int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, void* stream) {
     if (n_jobs <= 0 || B <= 0) return 0;
-    int per = (B + kThreads / 64 - 1) / (kThreads / 64);
-    hipLaunchKernelGGL(csr_scatter_kernel, dim3((unsigned)(n_jobs * per)), dim3(kThreads), 0, (hipStream_t)stream,
-                       jobs_dev, B, per, factor);
+    int per = (B + kScatterRows - 1) / kScatterRows;
+    hipLaunchKernelGGL(csr_scatter_kernel, dim3((unsigned)(n_jobs * per)), dim3(kScatterThreads), 0,
+                       (hipStream_t)stream, jobs_dev, B, per, factor);
     return launch_status();
 }
 
