@@ -328,3 +328,38 @@ def test_random_walks_of_the_untimed_model(case):
         h.run()
         assert not h.stalled
         assert m.final(m.replay(h.trace))
+
+
+# ---- Section 5's two worked examples of skipping iterations ---------------------------------------
+@pytest.mark.parametrize("which", ["a", "b"])
+def test_skipping_worked_examples(which):
+    """Three fully connected workers, A slow.  (a) staleness bound 4: B and C get 4 iterations ahead
+    and block; when A finishes its iteration it jumps to theirs (iteration 9) and they run another 4
+    before A moves again.  (b) one backup worker, max_ig 5: the same with 5, A jumps to 10."""
+    g = golden("token_queue_example.txt")
+    bound, jump_to, more = (int(g["skip_%s_%s" % (which, k)]) for k in ("bound", "jump_to", "more_iterations"))
+    s, b, ig = (bound, 0, 0) if which == "a" else (0, 1, bound)
+    a_at = jump_to - bound                                # the iteration A is stuck in
+    K = 40
+    unit = rng.TICKS_PER_UNIT
+    table = np.full((3, K), unit, dtype=np.uint64)
+    table[0, a_at:] = 1000 * unit                         # A is fast up to a_at, then very slow
+    h = protocol.Hop(inputs.complete(3), inputs.uniform_weights(inputs.complete(3)), s, b, K, max_ig=ig,
+                     skip_on=True, max_skip=10, delay_kind=rng.DELAY_TABLE, table=table, check=True, trace=True)
+    h.run()
+    it, seen_jump, after = [0, 0, 0], False, None
+    for item in h.trace:
+        if item[0] == "enter":
+            it[item[1]] = item[2]
+            if not seen_jump and item[1] != 0:
+                assert item[2] - it[0] <= bound           # never more than `bound` ahead of A
+        if item[0] == "jump" and item[1] == 0 and not seen_jump:
+            seen_jump = True
+            assert it[1] == it[2] == a_at + bound == jump_to   # B and C were blocked `bound` ahead
+            assert item[2] == jump_to                           # A jumps exactly to their iteration
+            after = jump_to
+        if seen_jump and item[0] == "jump" and item[1] == 0 and item[2] != jump_to:
+            break                                         # A's next move
+        if seen_jump and item[0] == "enter" and item[1] != 0:
+            after = max(after, item[2])
+    assert seen_jump and after == jump_to + more          # another `more` iterations, then blocked again
