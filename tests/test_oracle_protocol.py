@@ -363,3 +363,18 @@ def test_skipping_worked_examples(which):
         if seen_jump and item[0] == "enter" and item[1] != 0:
             after = max(after, item[2])
     assert seen_jump and after == jump_to + more          # another `more` iterations, then blocked again
+
+
+def test_backup_example_state_of_the_figure():
+    """Section 3.4: "worker A is stuck at iteration 0, while worker B and C are able to advance to
+    iteration 3 and 4": with one update needed, C (faster) runs one iteration ahead of B and never
+    more, since it needs B's update of the same iteration."""
+    nb = inputs.complete(3)
+    h = run(nb, 0, 1, 12, max_ig=20, mult=[NEVER, 1.0, 0.5], trace=True)
+    it, states = [0, 0, 0], set()
+    for item in h.trace:
+        if item[0] == "enter":
+            it[item[1]] = item[2]
+            states.add(tuple(it))
+            assert it[2] - it[1] <= 1 and it[0] == 0
+    assert (0, 3, 4) in states
