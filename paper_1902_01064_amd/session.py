@@ -41,6 +41,15 @@ class Session:
         r = self.arena[: self.N * self.D * self.stride].view(self.N, self.D, self.stride)[:, :, : self.d]
         return r.cpu().numpy()
 
+    def upload_rings(self, rings):
+        """Overwrite every ring slot with a [N, D, d] fp32 numpy array."""
+        r = self.arena[: self.N * self.D * self.stride].view(self.N, self.D, self.stride)[:, :, : self.d]
+        r.copy_(torch.from_numpy(rings).to(self.dev))
+
+    def upload_vel(self, vel):
+        v = self.arena[self.arena.numel() - self.N * self.stride:].view(self.N, self.stride)[:, : self.d]
+        v.copy_(torch.from_numpy(vel).to(self.dev))
+
     def vel_snapshot(self):
         """[N, d] numpy copy of the velocities (contexts with momentum: the arena's last N slots)."""
         v = self.arena[self.arena.numel() - self.N * self.stride:].view(self.N, self.stride)[:, : self.d]

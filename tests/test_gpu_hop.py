@@ -102,8 +102,16 @@ def attach(sess, c, p0, data):
     sess.set_params(p0)
 
 
+def read_active(sess, sched, recs):
+    """Which minibatch samples the kernel treated as active, per STEP record (from its coefficients)."""
+    return {(r.worker, r.k): sess.coef(e) != 0 for e, r in enumerate(recs) if r.kind == protocol.STEP}
+
+
 def run_parity(c, per_wave_check=True):
-    """Whole run on the GPU and in the oracle; returns worst per-record and end-of-run errors."""
+    """Whole run on the GPU and in the oracle.  The oracle never takes a value from the GPU: the run
+    as a whole starts both from p0, and the per-record check loads the ORACLE's state into the rings
+    before every wave.  (The one GPU decision the oracle follows is which side of the hinge a margin
+    within rounding of 1 fell on.)"""
     print("parity", c["name"], "N=%d d=%d K=%d" % (c["N"], c["d"], c["K"]), flush=True)
     p0, data = make_data(c)
     h, recs = oracle_schedule(c, c["K"])
@@ -115,52 +123,57 @@ def run_parity(c, per_wave_check=True):
         base, scale_of = oracle_grad(c, data)
         has_hinge = c["model"] in ("dense", "csr") and c.get("loss", 0) == 0
         mu = float(c.get("momentum", 0.0))
-        worst_step = strict_step = 0.0
-        gpu_active = {}
-        # ---- every record on its own: oracle arithmetic on the GPU's own inputs of that wave ----
-        for w in range(sched.n_waves):
-            before = sess.ring_snapshot() if per_wave_check else None
-            vel_before = sess.vel_snapshot() if per_wave_check and mu > 0 else None
-            sess.step(w, w + 1)
-            sess.sync()
-            members = [int(e) for e in sched.wave_order[sched.wave_begin[w]:sched.wave_begin[w + 1]]]
-            if has_hinge:
-                for e in members:
-                    if recs[e].kind == protocol.STEP:
-                        gpu_active[(recs[e].worker, recs[e].k)] = sess.coef(e) != 0
-            if not per_wave_check:
-                continue
-            after = sess.ring_snapshot()
-            vel_after = sess.vel_snapshot() if mu > 0 else None
-            for e in members:
-                r = recs[e]
-                grad = FollowKernelAtTies(base, gpu_active, scale_of) if has_hinge else base
-                vecs = [before[j, sl] for j, sl in zip(r.src_worker, r.src_slot)]
-                g = grad(r.worker, r.k, vecs[0]) if r.kind == protocol.STEP else None
-                if mu > 0 and r.kind == protocol.STEP and c["model"] != "none":
-                    g, v32 = arith.momentum_step(vel_before[r.worker], g, mu)
-                    worst_step = max(worst_step, rel_err(vel_after[r.worker], v32))
-                ref = arith.reduce_apply(vecs, r.w32, g, c["lr"])
-                worst_step = max(worst_step, rel_err(after[r.worker, r.out_slot], ref))
-                strict_step = max(strict_step, strict_rel_err(after[r.worker, r.out_slot], ref))
-        assert worst_step <= STEP_TOL, worst_step
-        # ---- the run as a whole: the oracle from p0 in sequence order ----
-        rings = arith.init_rings(p0.numpy(), c["N"], h.D)
+        N, d = c["N"], c["d"]
+
+        # ---- the run as a whole: both sides from p0, the oracle in sequence order ----
+        sess.step()
+        sess.sync()
+        gpu_active = read_active(sess, sched, recs) if has_hinge else {}
+        rings = arith.init_rings(p0.numpy(), N, h.D)
         grad = FollowKernelAtTies(base, gpu_active, scale_of) if has_hinge else base
-        vel = np.zeros((c["N"], c["d"]), dtype=np.float32) if mu > 0 else None
+        vel = np.zeros((N, d), dtype=np.float32) if mu > 0 else None
         ver = arith.execute(recs, rings, grad, c["lr"], vel=vel, mu=mu)
         want = arith.final_params(rings, ver)
         got, its = sess.params()
-        assert its == ver == [c["K"]] * c["N"]
+        assert its == ver == [c["K"]] * N
         if mu > 0:
             assert rel_err(sess.vel_snapshot(), vel) <= RUN_TOL
-        gotn = [got[i].cpu().numpy() for i in range(c["N"])]
-        worst_run = max(rel_err(gotn[i], want[i]) for i in range(c["N"]))
-        strict_run = max(strict_rel_err(gotn[i], want[i]) for i in range(c["N"]))
+        gotn = [got[i].cpu().numpy() for i in range(N)]
+        worst_run = max(rel_err(gotn[i], want[i]) for i in range(N))
+        strict_run = max(strict_rel_err(gotn[i], want[i]) for i in range(N))
+        flips = grad.flips if has_hinge else 0
+
+        # ---- every record on its own: before each wave the rings hold the oracle's state ----
+        worst_step = strict_step = 0.0
+        if per_wave_check:
+            sess.set_params(p0)
+            rings = arith.init_rings(p0.numpy(), N, h.D)
+            vel = np.zeros((N, d), dtype=np.float32) if mu > 0 else None
+            for w in range(sched.n_waves):
+                sess.upload_rings(rings)
+                if mu > 0:
+                    sess.upload_vel(vel)
+                sess.step(w, w + 1)
+                sess.sync()
+                members = [int(e) for e in sched.wave_order[sched.wave_begin[w]:sched.wave_begin[w + 1]]]
+                active = {(recs[e].worker, recs[e].k): sess.coef(e) != 0
+                          for e in members if has_hinge and recs[e].kind == protocol.STEP}
+                after = sess.ring_snapshot()
+                vel_after = sess.vel_snapshot() if mu > 0 else None
+                grad = FollowKernelAtTies(base, active, scale_of) if has_hinge else base
+                for e in members:         # members of a wave touch no slot in a conflicting way
+                    r = recs[e]
+                    ref = arith.apply_record(rings, r, grad, c["lr"], vel, mu)
+                    worst_step = max(worst_step, rel_err(after[r.worker, r.out_slot], ref))
+                    strict_step = max(strict_step, strict_rel_err(after[r.worker, r.out_slot], ref))
+                    if mu > 0 and r.kind == protocol.STEP and c["model"] != "none":
+                        worst_step = max(worst_step, rel_err(vel_after[r.worker], vel[r.worker]))
+                flips += grad.flips if has_hinge else 0
+            assert worst_step <= STEP_TOL, worst_step
         print("  records %d waves %d jumps %d  per-record err %.2e (floor 1e-3 rms: %.2e)  end-of-run err "
               "%.2e (floor 1e-3 rms: %.2e)  ties followed %d"
-              % (len(recs), sched.n_waves, sched.n_jumps, worst_step, strict_step, worst_run, strict_run,
-                 grad.flips if has_hinge else 0), flush=True)
+              % (len(recs), sched.n_waves, sched.n_jumps, worst_step, strict_step, worst_run, strict_run, flips),
+              flush=True)
         assert worst_run <= RUN_TOL, worst_run
         return worst_step, worst_run
     finally:
@@ -312,8 +325,9 @@ class _DeviceRows:
 @pytest.mark.parametrize("cfgn,n_records", [(2, 24), (3, 24), (5, 30)])
 def test_full_size_first_records(cfgn, n_records):
     """Configs 2, 3 and 5 at their real N, d, B, nnz and rows per worker, data generated on the
-    device: the first waves of the schedule, every record checked on its own against the oracle
-    (which gets the same inputs: the slots the record reads, copied back before the wave runs)."""
+    device: the first waves of the schedule, every record checked on its own against the oracle.
+    Before a wave runs, the slots it reads are overwritten with the oracle's own versions, so the
+    oracle never computes from a value the GPU produced."""
     c = inputs.config(cfgn)
     print("parity", c["name"], "full size: N=%d d=%d rows=%d" % (c["N"], c["d"], c["rows"]), flush=True)
     h, recs = oracle_schedule(c, c["K"])
@@ -339,28 +353,33 @@ def test_full_size_first_records(cfgn, n_records):
                                  for r in rows])
         done, worst, strict, w = 0, 0.0, 0.0, 0
         gpu_active = {}
+        p0n = p0.cpu().numpy()
+        mine = {}                      # the oracle's own versions of the slots written so far
         while done < n_records and w < sched.n_waves:
             members = [int(e) for e in sched.wave_order[sched.wave_begin[w]:sched.wave_begin[w + 1]]]
-            members = members[: max(1, n_records - done)] if done + len(members) > n_records + 8 else members
-            before = {}
+            # the rings get the oracle's state of every slot this wave reads (slot 0 still holds p0)
             for e in members:
                 for j, sl in zip(recs[e].src_worker, recs[e].src_slot):
-                    if (j, sl) not in before:
-                        before[(j, sl)] = sess.slot(j, sl).cpu().numpy()
+                    if (j, sl) in mine:
+                        sess.slot(j, sl).copy_(torch.from_numpy(mine[(j, sl)]).to(sess.dev))
             sess.step(w, w + 1)
             sess.sync()
+            outs = {}
             for e in members:
                 r = recs[e]
                 if r.kind == protocol.STEP:
                     gpu_active[(r.worker, r.k)] = sess.coef(e) != 0
                 grad = FollowKernelAtTies(base, gpu_active, scale_of)
-                vecs = [before[(j, sl)] for j, sl in zip(r.src_worker, r.src_slot)]
+                vecs = [mine.get((j, sl), p0n) for j, sl in zip(r.src_worker, r.src_slot)]
+                assert all((j, sl) in mine or sl == 0 for j, sl in zip(r.src_worker, r.src_slot))
                 g = grad(r.worker, r.k, vecs[0]) if r.kind == protocol.STEP else None
                 ref = arith.reduce_apply(vecs, r.w32, g, c["lr"])
+                outs[(r.worker, r.out_slot)] = ref
                 got = sess.slot(r.worker, r.out_slot).cpu().numpy()
                 worst = max(worst, rel_err(got, ref))
                 strict = max(strict, strict_rel_err(got, ref))
                 done += 1
+            mine.update(outs)
             w += 1
         print("  %d records in %d waves: per-record err %.2e (floor 1e-3 rms: %.2e)" % (done, w, worst, strict),
               flush=True)
