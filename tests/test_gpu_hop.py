@@ -430,3 +430,30 @@ def test_out_of_order_delivery(cfgn, over):
     """Updates that overtake each other on an edge (Section 6.1): deeper rings (s + max_ig + 2 slots),
     same parity bars."""
     run_parity(inputs.config(cfgn, **over))
+
+
+def test_gpu_run_equals_matrix_power_without_the_oracle():
+    """Independent of the oracle's code: standard mode (s = 0, b = 0), zero gradient, random delays.
+    Whatever the schedule, x_K = (W^T)^K x_0 (standard-training figure without the gradient), and a
+    doubly stochastic W keeps the replica mean (Section 3.1)."""
+    nb = inputs.torus(4, 4)
+    W = inputs.metropolis_weights(nb)
+    N, d, K = 16, 4096 + 4, 12
+    c = dict(name="matrix power", in_nbrs=nb, W=W, N=N, d=d, s=0, b=0, max_ig=3, skip_on=False, max_skip=10,
+             trigger=1, lr=0.1, lam=0.0, batch=0, rows=0, seed=5, delay_kind=hop.HOP_DELAY_EXP1,
+             mult=[1.0 + (i % 3) for i in range(N)], K=K, model="none")
+    X0 = torch.randn(N, d, generator=torch.Generator().manual_seed(9))
+    sess = Session(c)
+    try:
+        sess.set_params(X0)
+        sess.simulate()
+        sess.step()
+        sess.sync()
+        got, its = sess.params()
+        assert its == [K] * N
+        got = np.stack([g.cpu().numpy() for g in got]).astype(np.float64)
+    finally:
+        sess.close()
+    want = np.linalg.matrix_power(W.astype(np.float64).T, K) @ X0.numpy().astype(np.float64)
+    assert np.max(np.abs(got - want)) <= 1e-5 * np.max(np.abs(want))
+    assert np.allclose(got.mean(0), X0.numpy().astype(np.float64).mean(0), atol=2e-6)
