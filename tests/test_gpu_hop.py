@@ -457,3 +457,32 @@ def test_gpu_run_equals_matrix_power_without_the_oracle():
     want = np.linalg.matrix_power(W.astype(np.float64).T, K) @ X0.numpy().astype(np.float64)
     assert np.max(np.abs(got - want)) <= 1e-5 * np.max(np.abs(want))
     assert np.allclose(got.mean(0), X0.numpy().astype(np.float64).mean(0), atol=2e-6)
+
+
+def test_degenerate_shapes():
+    """One worker (no neighbours), two workers, d = 1 and d = 5, minibatch of one sample, K = 0."""
+    for n, d, K, B in [(1, 5, 6, 1), (2, 1, 5, 2), (2, 7, 0, 3), (3, 1030, 4, 1024)]:
+        nb = inputs.ring(n)
+        c = dict(name="degenerate N=%d d=%d" % (n, d), in_nbrs=nb, W=inputs.uniform_weights(nb), N=n, d=d, s=1,
+                 b=0, max_ig=0, skip_on=False, max_skip=10, trigger=1, lr=0.05, lam=1e-3, batch=B, rows=1100,
+                 seed=3, delay_kind=hop.HOP_DELAY_EXP1, mult=None, K=K, model="dense")
+        p0, data = make_data(c)
+        h, recs = oracle_schedule(c, K)
+        sess = Session(c)
+        try:
+            attach(sess, c, p0, data)
+            sched = sess.simulate()
+            assert sched.n_records == len(recs) == n * K
+            sess.step()
+            sess.sync()
+            got, its = sess.params()
+            assert its == [K] * n
+            base, scale_of = oracle_grad(c, data)
+            active = read_active(sess, sched, recs)
+            rings = arith.init_rings(p0.numpy(), n, h.D)
+            ver = arith.execute(recs, rings, FollowKernelAtTies(base, active, scale_of), c["lr"])
+            want = arith.final_params(rings, ver)
+            for i in range(n):
+                assert rel_err(got[i].cpu().numpy(), want[i]) <= RUN_TOL
+        finally:
+            sess.close()
