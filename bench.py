@@ -149,6 +149,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--d", type=int, default=0, help="override the parameter count (not a valid bench line)")
+    ap.add_argument("--momentum", type=float, default=0.0, help="per-worker momentum (not the default bench line)")
+    ap.add_argument("--log-loss", action="store_true", help="log loss instead of hinge (SVM configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the brief runs of the other configs")
     ap.add_argument("--graph", action="store_true",
@@ -173,7 +175,12 @@ def main():
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
-    res, c, p0 = run_config(args.config, args.steps, args.warmup, args.graph, {"d": args.d} if args.d else None)
+    over = {"d": args.d} if args.d else {}
+    if args.momentum:
+        over["momentum"] = args.momentum
+    if args.log_loss:
+        over["loss"] = 1
+    res, c, p0 = run_config(args.config, args.steps, args.warmup, args.graph, over or None)
     mix = res["mix"]
     out = {
         "metric": METRIC,
@@ -200,7 +207,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         from oracle import protocol
-        if c["model"] == "synth":
+        if c["model"] == "synth" and not args.momentum:
             h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], c["K"], max_ig=c["max_ig"],
                              skip_on=c["skip_on"], max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
                              delay_kind=c["delay_kind"], mult=c["mult"], check=False)
@@ -208,7 +215,7 @@ def main():
         else:
             out["cpu_baseline"] = None
     del p0
-    if not args.no_others and not args.d:
+    if not args.no_others and not over:
         others = {}
         for n in (1, 2, 3, 5):
             if n == args.config:
