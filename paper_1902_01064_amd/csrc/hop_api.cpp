@@ -149,9 +149,12 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                     gj.val = dd.val;
                     gj.y = dd.y;
                     if (c->vel) {
-                        // a velocity is dense, so the gradient is materialised: g = lambda w, sparse part added
-                        gj.out = gj.g;
-                        mj.g = gj.g;
+                        // with a velocity, lambda w goes into it inside the mix (v <- mu v + lambda x_self) and the
+                        // sparse part is scattered into both the velocity (-c x) and the result (+eta c x)
+                        mj.vel = c->vel + (int64_t)i * c->stride;
+                        mj.mu = c->opts.momentum;
+                        mj.lam_fold = c->opts.lambda;
+                        gj.vel = mj.vel;
                     } else {
                         // lambda w folds into the self term: sum_a w'_a x_a - eta lambda x_self - eta (sparse part)
                         mj.w[0] = mj.w[0] - eta * c->opts.lambda;
@@ -166,7 +169,7 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                     want_job = false;
                 }
                 if (want_job) grad.push_back(gj);
-                if (c->vel && mj.g) {
+                if (c->vel && mj.g && !mj.vel) {
                     mj.vel = c->vel + (int64_t)i * c->stride;
                     mj.mu = c->opts.momentum;
                 }
@@ -534,15 +537,15 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
         } else if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
             HOP_LAUNCH(c, hopk_csr_margin(gj, ng, B, c->opts.loss, stream));
-            if (c->vel) HOP_LAUNCH(c, hopk_csr_dense_grad(gj, ng, B, c->d, c->opts.lambda, stream));
             if (timed && (rc = prof_end(c))) return rc;
         }
         if (timed && (rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
         HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, stream));
         if (timed && (rc = prof_end(c))) return rc;
-        if (ng > 0 && mode == HOP_GRAD_SVM_CSR && !c->vel) {
+        if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, 0.0))) return rc;
-            HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, c->opts.lr, stream));
+            HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, c->opts.lr, 0, stream));
+            if (c->vel) HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, -1.0f, 1, stream));
             if (timed && (rc = prof_end(c))) return rc;
         }
     }

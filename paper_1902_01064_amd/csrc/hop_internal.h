@@ -16,7 +16,7 @@ struct alignas(16) HopMixJob {
     float eta;
     int32_t A;
     float mu;
-    int32_t pad0;
+    float lam_fold;            // with vel: v <- mu v + g + lam_fold * src[0] (the dense part of a sparse gradient)
     const float* src[HOP_MAX_A];
     float w[HOP_MAX_A];
 };
@@ -34,6 +34,7 @@ struct alignas(16) HopGradJob {
     float* coef;               // B hinge coefficients of this record
     float* partial;            // dense: B x nseg partial dot products
     float* out;                // csr: the vector the sparse part is scattered into
+    float* vel;                // csr with momentum: the velocity the sparse part is scattered into as well
     uint32_t k0, k1, k2;       // synth: hash keys of (seed, worker, iteration)
     float scale;               // synth: fp32 factor
 };
@@ -44,7 +45,7 @@ int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream);
 int hopk_dense_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, void* stream);
 int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, int loss, void* stream);
 int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, void* stream);
-int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float eta, void* stream);
+int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, int into_velocity, void* stream);
 int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream);
 int hopk_copy(void* dst, const void* src, size_t bytes, void* stream);
 int hopk_dense_nseg(int64_t d);                 // column segments per row in the margin pass

@@ -77,6 +77,7 @@ __device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int6
     const float neg_eta = -job->eta;
     float* vel = job->vel;
     const float mu = job->mu;
+    const float lam_fold = job->lam_fold;
     float* out = job->out;
     float4 acc[VEC];
     int64_t idx[VEC];
@@ -114,6 +115,11 @@ __device__ __forceinline__ void mix_tile(const HopMixJob* __restrict__ job, int6
         for (int u = 0; u < VEC; ++u) {
             float4 v = ok[u] ? ld_once<NT>(vel, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
             float4 gg = (ok[u] && g != nullptr) ? ld_once<NT>(g, idx[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (lam_fold != 0.f && ok[u]) {      // dense part lambda w of a gradient whose sparse part is scattered later
+                const float4 x0 = ld_src<NT>(job->src[0], idx[u]);
+                gg = make_float4(fmaf(lam_fold, x0.x, gg.x), fmaf(lam_fold, x0.y, gg.y), fmaf(lam_fold, x0.z, gg.z),
+                                 fmaf(lam_fold, x0.w, gg.w));
+            }
             v = make_float4(fmaf(mu, v.x, gg.x), fmaf(mu, v.y, gg.y), fmaf(mu, v.z, gg.z), fmaf(mu, v.w, gg.w));
             if (ok[u]) st_once<NT>(vel, idx[u], v);
             acc[u].x = fmaf(neg_eta, v.x, acc[u].x);
@@ -158,6 +164,11 @@ __device__ __forceinline__ void mix_tile_any(const HopMixJob* __restrict__ job, 
         }
         if (job->vel != nullptr) {
             float4 gg = g != nullptr ? ld_once<NT>(g, i) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (job->lam_fold != 0.f) {
+                const float4 x0 = ld_src<NT>(job->src[0], i);
+                const float lf = job->lam_fold;
+                gg = make_float4(fmaf(lf, x0.x, gg.x), fmaf(lf, x0.y, gg.y), fmaf(lf, x0.z, gg.z), fmaf(lf, x0.w, gg.w));
+            }
             v = ld_once<NT>(job->vel, i);
             const float mu = job->mu;
             v = make_float4(fmaf(mu, v.x, gg.x), fmaf(mu, v.y, gg.y), fmaf(mu, v.z, gg.z), fmaf(mu, v.w, gg.w));
@@ -253,7 +264,8 @@ __global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jo
             float acc = job->w[0] * job->src[0][c];
             for (int a = 1; a < job->A; ++a) acc = fmaf(job->w[a], job->src[a][c], acc);
             if (job->vel != nullptr) {
-                float v = fmaf(job->mu, job->vel[c], job->g != nullptr ? job->g[c] : 0.f);
+                float v = fmaf(job->mu, job->vel[c],
+                               fmaf(job->lam_fold, job->src[0][c], job->g != nullptr ? job->g[c] : 0.f));
                 job->vel[c] = v;
                 acc = fmaf(-job->eta, v, acc);
             } else if (job->g != nullptr) {
@@ -518,14 +530,15 @@ constexpr int kScatterRows = kScatterThreads / 64;
 constexpr int kHotCols = 1024;
 
 __global__ __launch_bounds__(kScatterThreads) void csr_scatter_kernel(const HopGradJob* __restrict__ jobs, int B,
-                                                                      int blocks_per_job, float factor) {
+                                                                      int blocks_per_job, float factor,
+                                                                      int into_velocity) {
     __shared__ float hot[kHotCols];
     const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const HopGradJob* job = jobs + blockIdx.x / blocks_per_job;
     const int m = (blockIdx.x % blocks_per_job) * kScatterRows + wv;
     for (int i = threadIdx.x; i < kHotCols; i += kScatterThreads) hot[i] = 0.f;
     __syncthreads();
-    float* target = job->out;
+    float* target = into_velocity ? job->vel : job->out;
     if (m < B) {
         const float c = job->coef[m];
         if (c != 0.f) {
@@ -665,11 +678,11 @@ int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, voi
     return launch_status();
 }
 
-int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, void* stream) {
+int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, int into_velocity, void* stream) {
     if (n_jobs <= 0 || B <= 0) return 0;
     int per = (B + kScatterRows - 1) / kScatterRows;
     hipLaunchKernelGGL(csr_scatter_kernel, dim3((unsigned)(n_jobs * per)), dim3(kScatterThreads), 0,
-                       (hipStream_t)stream, jobs_dev, B, per, factor);
+                       (hipStream_t)stream, jobs_dev, B, per, factor, into_velocity);
     return launch_status();
 }
 
@@ -682,7 +695,7 @@ int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d
                        n_jobs, d, lambda, n_chunks);
     int rc = launch_status();
     if (rc) return rc;
-    return hopk_csr_scatter(jobs_dev, n_jobs, B, -1.0f, stream);
+    return hopk_csr_scatter(jobs_dev, n_jobs, B, -1.0f, 0, stream);
 }
 
 int hopk_copy(void* dst, const void* src, size_t bytes, void* stream) {
