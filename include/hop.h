@@ -202,7 +202,10 @@ int hop_set_rows(hop_ctx* ctx, int32_t worker, int64_t rows);
  * hop_simulate: the minibatch ids of a schedule are drawn for the row counts known then, and hop_step
  * returns HOP_ERR_STATE if a worker's row count has changed since. */
 int hop_set_data_dense(hop_ctx* ctx, int32_t worker, const float* X, const float* y, int64_t rows);
-/* CSR features: rowptr int64 [rows+1], col int32 ascending per row, val fp32; labels y; device. */
+/* CSR features: rowptr int64 [rows+1], col int32 ascending per row, val fp32; labels y; device.
+ * The call checks on the device that rowptr is non-decreasing and every column id lies in [0, d)
+ * (the kernels index parameter vectors with them) and returns HOP_ERR_INVALID_ARG otherwise; it
+ * synchronises the stream. */
 int hop_set_data_csr(hop_ctx* ctx, int32_t worker, const int64_t* rowptr, const int32_t* col,
                      const float* val, const float* y, int64_t rows);
 /* Where STEP records take their gradient from.  variance: HOP_GRAD_SYNTH only.  external:

@@ -426,6 +426,23 @@ int hop_set_data_csr(hop_ctx* c, int32_t worker, const int64_t* rowptr, const in
     if (!c || worker < 0 || worker >= c->N || !rowptr || !col || !val || !y || rows < 1 || rows > 0x7FFFFFFFll)
         return HOP_ERR_INVALID_ARG;
     if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    {
+        // The gather and scatter kernels index parameter vectors with these column ids: check on the
+        // device, once, that the row pointers are ordered and every id lies in [0, d).
+        hipStream_t st = (hipStream_t)c->stream;
+        int64_t ends[2] = {0, 0};
+        HOP_HIP(c, hipStreamSynchronize(st));
+        HOP_HIP(c, hipMemcpy(&ends[0], rowptr, sizeof(int64_t), hipMemcpyDeviceToHost));
+        HOP_HIP(c, hipMemcpy(&ends[1], rowptr + rows, sizeof(int64_t), hipMemcpyDeviceToHost));
+        if (ends[0] < 0 || ends[1] < ends[0]) return HOP_ERR_INVALID_ARG;
+        int* flag = reinterpret_cast<int*>(c->partial);       // scratch of the context, idle between passes
+        HOP_HIP(c, hipMemsetAsync(flag, 0, sizeof(int), st));
+        HOP_LAUNCH(c, hopk_csr_check(rowptr, col, rows, ends[0], ends[1] - ends[0], c->d, flag, c->stream));
+        int bad = 0;
+        HOP_HIP(c, hipMemcpyAsync(&bad, flag, sizeof(int), hipMemcpyDeviceToHost, st));
+        HOP_HIP(c, hipStreamSynchronize(st));
+        if (bad) return HOP_ERR_INVALID_ARG;
+    }
     HopData dd;
     dd.rows = rows;
     dd.rowptr = rowptr;

@@ -47,6 +47,8 @@ int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, fl
 int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, void* stream);
 int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, int into_velocity, void* stream);
 int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream);
+int hopk_csr_check(const int64_t* rowptr, const int32_t* col, int64_t rows, int64_t first, int64_t nnz, int64_t d,
+                   int* flag_dev, void* stream);
 int hopk_copy(void* dst, const void* src, size_t bytes, void* stream);
 int hopk_dense_nseg(int64_t d);                 // column segments per row in the margin pass
 

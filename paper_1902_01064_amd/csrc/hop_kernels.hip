@@ -573,6 +573,21 @@ __global__ __launch_bounds__(kThreads) void scale_kernel(const HopGradJob* __res
     }
 }
 
+// Input check for CSR data: rowptr non-decreasing over [0, rows], every column id inside [0, d).
+// flag[0] becomes 1 on any violation.
+__global__ __launch_bounds__(kThreads) void csr_check_kernel(const int64_t* __restrict__ rowptr,
+                                                             const int32_t* __restrict__ col, int64_t rows,
+                                                             int64_t first, int64_t nnz, int64_t d, int* flag) {
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    bool bad = false;
+    if (t < rows) bad = rowptr[t] > rowptr[t + 1] || rowptr[t] < first;
+    if (t < nnz) {
+        const int32_t c = col[first + t];
+        bad = bad || c < 0 || (int64_t)c >= d;
+    }
+    if (bad) atomicExch(flag, 1);
+}
+
 __global__ __launch_bounds__(kThreads) void copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src,
                                                         int64_t n16) {
     int64_t i = (int64_t)blockIdx.x * (kThreads * 4) + threadIdx.x;
@@ -696,6 +711,17 @@ int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d
     int rc = launch_status();
     if (rc) return rc;
     return hopk_csr_scatter(jobs_dev, n_jobs, B, -1.0f, 0, stream);
+}
+
+int hopk_csr_check(const int64_t* rowptr, const int32_t* col, int64_t rows, int64_t first, int64_t nnz, int64_t d,
+                   int* flag_dev, void* stream) {
+    int64_t n = rows > nnz ? rows : nnz;
+    if (n <= 0) return 0;
+    int64_t grid = (n + kThreads - 1) / kThreads;
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(csr_check_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, rowptr, col,
+                       rows, first, nnz, d, flag_dev);
+    return launch_status();
 }
 
 int hopk_copy(void* dst, const void* src, size_t bytes, void* stream) {

@@ -486,3 +486,27 @@ def test_degenerate_shapes():
                 assert rel_err(got[i].cpu().numpy(), want[i]) <= RUN_TOL
         finally:
             sess.close()
+
+
+def test_csr_data_with_bad_indices_is_refused():
+    """A column id outside [0, d) or disordered row pointers would make the gather / scatter kernels
+    read and write out of bounds: hop_set_data_csr finds them on the device and refuses the data."""
+    c = inputs.config(3, d=4096, rows=64, K=2)
+    p0, data = make_data(c)
+    sess = Session(c)
+    try:
+        rp, col, val, y = [t.to(sess.dev).contiguous() for t in data[0]]
+        args = lambda rp_, col_: (sess.ctx, 0, rp_.data_ptr(), col_.data_ptr(), val.data_ptr(), y.data_ptr(), 64)
+        hop.hop_set_data_csr(*args(rp, col))                              # good data is accepted
+        for bad_col in (col.clone().index_fill_(0, torch.tensor([17], device=sess.dev), 4096),
+                        col.clone().index_fill_(0, torch.tensor([5], device=sess.dev), -1)):
+            with pytest.raises(hop.HopError) as e:
+                hop.hop_set_data_csr(*args(rp, bad_col))
+            assert e.value.code == hop.HOP_ERR_INVALID_ARG
+        bad_rp = rp.clone()
+        bad_rp[10] = bad_rp[12]
+        with pytest.raises(hop.HopError) as e:
+            hop.hop_set_data_csr(*args(bad_rp, col))
+        assert e.value.code == hop.HOP_ERR_INVALID_ARG
+    finally:
+        sess.close()
