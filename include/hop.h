@@ -254,7 +254,9 @@ int hop_profile_read(hop_ctx* ctx, int kernel, double* ms, int64_t* launches, do
  * hop_step these calls are synchronous: they upload a small descriptor (hipMalloc / hipFree inside),
  * launch on the given stream and wait for it.  All vectors must be 16-byte aligned (when d is a
  * multiple of 4 this includes every row of X); a misaligned or NULL pointer, A outside 1..HOP_MAX_A
- * or B outside 1..1024 gives HOP_ERR_INVALID_ARG and nothing is launched. */
+ * or B outside 1..1024 gives HOP_ERR_INVALID_ARG and nothing is launched.  The contents of device
+ * index arrays (sample ids in rows_dev, CSR row pointers and column ids) are NOT checked here: the
+ * caller guarantees ids in range, as hop_set_data_csr does for a context's data. */
 /* Fused Reduce + Apply for n_jobs independent jobs (host array), each over d columns. */
 int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* hip_stream);
 /* Linear-SVM minibatch (sub)gradient g = lambda w - sum_m c_m x_{r_m}; hinge: c_m = y/B if
