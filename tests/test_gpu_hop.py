@@ -510,3 +510,44 @@ def test_csr_data_with_bad_indices_is_refused():
         assert e.value.code == hop.HOP_ERR_INVALID_ARG
     finally:
         sess.close()
+
+
+def test_vector_longer_than_2_to_31_elements():
+    """Maximum size: parameter vectors of 2^31 + 12 291 floats (8.6 GB each, ragged tail of 3), so
+    element indices pass 2^31 and byte offsets 2^33 inside one vector.  Two workers, standard mode,
+    synthetic gradients, three iterations; the oracle follows sampled columns, among them both ends
+    and the columns around 2^31."""
+    d = (1 << 31) + 3 * 4096 + 3
+    nb = inputs.complete(2)
+    c = dict(inputs.config(4, d=d, K=3), in_nbrs=nb, W=inputs.uniform_weights(nb), N=2, s=0, b=0,
+             skip_on=False, mult=[1.0, 1.0], name="max-d")
+    free, _ = torch.cuda.mem_get_info()
+    if free < 110 * (1 << 30):
+        pytest.skip("needs 110 GB of free HBM")
+    print("parity", c["name"], "d =", d, flush=True)
+    h, recs = oracle_schedule(c, c["K"])
+    cols = np.unique(np.concatenate([
+        np.random.default_rng(2).integers(0, d, size=1 << 12), np.arange(0, 64), np.arange(d - 64, d),
+        np.arange((1 << 31) - 64, (1 << 31) + 64)]))
+    p0 = inputs.initial_params(c["seed"], d, 0.01)
+    p0_cols = p0.numpy()[cols].copy()
+    sess = Session(c)
+    try:
+        hop.hop_set_grad_source(sess.ctx, hop.HOP_GRAD_SYNTH, c["grad_var"])
+        sess.set_params(p0)
+        del p0
+        sched = sess.simulate()
+        assert_schedule_equal(sched, h, recs)
+        sess.step()
+        sess.sync()
+        got, its = sess.params()
+        rings = arith.init_rings(p0_cols, 2, h.D)
+        ver = arith.execute(recs, rings, arith.GradSynth(c["seed"], c["grad_var"], cols), c["lr"])
+        want = arith.final_params(rings, ver)
+        assert its == ver == [3, 3]
+        idx = torch.from_numpy(cols).to(sess.dev)
+        worst = max(rel_err(got[i][idx].cpu().numpy(), want[i]) for i in range(2))
+        print("  end-of-run err on %d sampled columns: %.2e" % (len(cols), worst), flush=True)
+        assert worst <= STEP_TOL * 3
+    finally:
+        sess.close()
