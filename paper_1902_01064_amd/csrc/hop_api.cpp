@@ -551,16 +551,16 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
             HOP_LAUNCH(c, hopk_dense_margin(gj, ng, B, c->d, stream));
             HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, c->opts.loss, stream));
             if (timed && (rc = prof_end(c))) return rc;
-        } else if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
-            if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
-            HOP_LAUNCH(c, hopk_csr_margin(gj, ng, B, c->opts.loss, stream));
-            if (timed && (rc = prof_end(c))) return rc;
         }
+        const bool csr = ng > 0 && mode == HOP_GRAD_SVM_CSR;
         if (timed && (rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
-        HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, stream));
+        if (csr)   // margins and Reduce + Apply both only read x_k: one launch
+            HOP_LAUNCH(c, hopk_mix_csr_margin(s->mix_dev + jb, nj, c->d, gj, ng, B, c->opts.loss, stream));
+        else
+            HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, stream));
         if (timed && (rc = prof_end(c))) return rc;
-        if (ng > 0 && mode == HOP_GRAD_SVM_CSR) {
-            if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, 0.0))) return rc;
+        if (csr) {
+            if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
             HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, c->opts.lr, 0, stream));
             if (c->vel) HOP_LAUNCH(c, hopk_csr_scatter(gj, ng, B, -1.0f, 1, stream));
             if (timed && (rc = prof_end(c))) return rc;

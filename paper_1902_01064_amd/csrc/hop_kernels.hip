@@ -34,8 +34,7 @@ __device__ __forceinline__ void st4_stream(float* p, int64_t i4, float4 v) {
 // 8 different column chunks, and one XCD sees the same chunk for all jobs of a wave back to back:
 // a source vector read by several jobs (a worker and its neighbours all average it) is then
 // fetched from HBM once per XCD-local L2 instead of once per job.
-__device__ __forceinline__ bool map_block(int n_jobs, int64_t n_chunks, int* job, int64_t* chunk) {
-    int64_t b = blockIdx.x;
+__device__ __forceinline__ bool map_block(int64_t b, int n_jobs, int64_t n_chunks, int* job, int64_t* chunk) {
     int xcd = (int)(b % kXcd);
     int64_t local = b / kXcd;
     *job = (int)(local % n_jobs);
@@ -186,21 +185,23 @@ __device__ __forceinline__ void mix_tile_any(const HopMixJob* __restrict__ job, 
     }
 }
 
+// Work of one workgroup of the mix; `bid` is its index among the mix's workgroups (the launch may
+// hold other workgroups in front of them, which only rotates the assignment of XCDs).
 template <int VEC, int NT, int MAP, int T>
-__global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jobs, int n_jobs, int64_t d,
-                                                int64_t n_chunks) {
+__device__ __forceinline__ void mix_block(const HopMixJob* __restrict__ jobs, int n_jobs, int64_t d,
+                                          int64_t n_chunks, int64_t bid) {
     int j;
     int64_t chunk;
     if (MAP == 1) {
-        if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+        if (!map_block(bid, n_jobs, n_chunks, &j, &chunk)) return;
     } else if (MAP == 0) {
-        j = (int)(blockIdx.x / n_chunks);
-        chunk = blockIdx.x % n_chunks;
+        j = (int)(bid / n_chunks);
+        chunk = bid % n_chunks;
     } else if (MAP >= 10) {
         // XCD-aware like MAP 1, but every XCD owns runs of G = MAP - 10 consecutive chunks, and visits
         // them job by job: longer contiguous pieces of every stream are in flight at a time
         constexpr int G = MAP - 10;
-        int64_t b = blockIdx.x;
+        int64_t b = bid;
         int xcd = (int)(b % kXcd);
         int64_t local = b / kXcd;
         int sub = (int)(local % G);
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jo
         if (chunk >= n_chunks) return;
     } else if (MAP == 3) {
         // every XCD owns one contiguous eighth of the columns
-        int64_t b = blockIdx.x;
+        int64_t b = bid;
         int xcd = (int)(b % kXcd);
         int64_t local = b / kXcd;
         int64_t per_xcd = (n_chunks + kXcd - 1) / kXcd;
@@ -218,8 +219,8 @@ __global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jo
         chunk = xcd * per_xcd + local / n_jobs;
         if (local / n_jobs >= per_xcd || chunk >= n_chunks) return;
     } else {
-        j = (int)(blockIdx.x % n_jobs);
-        chunk = blockIdx.x / n_jobs;
+        j = (int)(bid % n_jobs);
+        chunk = bid / n_jobs;
     }
     const HopMixJob* job = jobs + j;
     const int64_t n4 = d >> 2;
@@ -277,7 +278,13 @@ __global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jo
 }
 
 template <int VEC, int NT, int MAP, int T>
-int launch_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
+__global__ __launch_bounds__(T) void mix_kernel(const HopMixJob* __restrict__ jobs, int n_jobs, int64_t d,
+                                                int64_t n_chunks) {
+    mix_block<VEC, NT, MAP, T>(jobs, n_jobs, d, n_chunks, blockIdx.x);
+}
+
+template <int VEC, int MAP, int T>
+int64_t mix_grid(int n_jobs, int64_t d, int64_t* n_chunks_out) {
     int64_t n4 = d >> 2;
     int64_t per = (int64_t)T * VEC;
     int64_t n_chunks = (n4 + per - 1) / per;
@@ -287,6 +294,14 @@ int launch_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
         int64_t span = (int64_t)kXcd * (MAP - 10);
         grid = (n_chunks + span - 1) / span * span * n_jobs;
     }
+    *n_chunks_out = n_chunks;
+    return grid;
+}
+
+template <int VEC, int NT, int MAP, int T>
+int launch_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
+    int64_t n_chunks;
+    int64_t grid = mix_grid<VEC, MAP, T>(n_jobs, d, &n_chunks);
     if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((mix_kernel<VEC, NT, MAP, T>), dim3((unsigned)grid), dim3(T), 0, (hipStream_t)stream,
                        jobs_dev, n_jobs, d, n_chunks);
@@ -326,7 +341,7 @@ __global__ __launch_bounds__(kThreads) void synth_kernel(const HopGradJob* __res
                                                          int64_t d, int64_t n_chunks) {
     int j;
     int64_t chunk;
-    if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    if (!map_block(blockIdx.x, n_jobs, n_chunks, &j, &chunk)) return;
     const HopGradJob* job = jobs + j;
     const uint32_t k0 = job->k0, k1 = job->k1, k2 = job->k2;
     const float scale = job->scale;
@@ -432,7 +447,7 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
     __shared__ int nactS;
     int j;
     int64_t chunk;
-    if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    if (!map_block(blockIdx.x, n_jobs, n_chunks, &j, &chunk)) return;
     const HopGradJob* job = jobs + j;
     const float invB = 1.0f / (float)B;
     for (int m = threadIdx.x; m < B; m += kThreads) {
@@ -504,11 +519,11 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
 
 // ------------------------------------------------------------------- CSR SVM: margins ----
 // One wavefront per (job, minibatch row): gather w[col], reduce across the 64 lanes.
-__global__ __launch_bounds__(kThreads) void csr_margin_kernel(const HopGradJob* __restrict__ jobs, int B,
-                                                              int rows_per_job_blocks, int loss) {
+__device__ __forceinline__ void csr_margin_block(const HopGradJob* __restrict__ jobs, int B,
+                                                 int rows_per_job_blocks, int loss, int bid) {
     const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const HopGradJob* job = jobs + blockIdx.x / rows_per_job_blocks;
-    const int m = (blockIdx.x % rows_per_job_blocks) * (kThreads / 64) + wv;
+    const HopGradJob* job = jobs + bid / rows_per_job_blocks;
+    const int m = (bid % rows_per_job_blocks) * (kThreads / 64) + wv;
     if (m >= B) return;
     const int r = job->rows[m];
     const int64_t lo = job->rowptr[r], hi = job->rowptr[r + 1];
@@ -517,6 +532,40 @@ __global__ __launch_bounds__(kThreads) void csr_margin_kernel(const HopGradJob* 
     for (int64_t p = lo + lane; p < hi; p += 64) acc = fmaf(job->val[p], w[job->col[p]], acc);
     acc = wave_sum(acc);
     if (lane == 0) job->coef[m] = loss_coef(job->y[r], acc, 1.0f / (float)B, loss);
+}
+
+__global__ __launch_bounds__(kThreads) void csr_margin_kernel(const HopGradJob* __restrict__ jobs, int B,
+                                                              int rows_per_job_blocks, int loss) {
+    csr_margin_block(jobs, B, rows_per_job_blocks, loss, (int)blockIdx.x);
+}
+
+// The margins of a wave's STEP records and the wave's Reduce + Apply in one launch: both only read
+// x_k, and nothing a wave writes is read inside it, so they need no order between them.  The few
+// latency-bound margin workgroups come first and run under the streaming ones.
+template <int VEC, int NT, int MAP>
+__global__ __launch_bounds__(kThreads) void mix_csr_margin_kernel(const HopMixJob* __restrict__ mix_jobs, int n_mix,
+                                                                  int64_t d, int64_t n_chunks,
+                                                                  const HopGradJob* __restrict__ grad_jobs, int B,
+                                                                  int rows_per_job_blocks, int loss,
+                                                                  int margin_blocks) {
+    if ((int)blockIdx.x < margin_blocks) {
+        csr_margin_block(grad_jobs, B, rows_per_job_blocks, loss, (int)blockIdx.x);
+        return;
+    }
+    mix_block<VEC, NT, MAP, kThreads>(mix_jobs, n_mix, d, n_chunks, (int64_t)blockIdx.x - margin_blocks);
+}
+
+template <int VEC, int NT, int MAP>
+int launch_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
+                          int loss, void* stream) {
+    int64_t n_chunks;
+    const int64_t grid = mix_grid<VEC, MAP, kThreads>(n_mix, d, &n_chunks);
+    const int per = (B + kThreads / 64 - 1) / (kThreads / 64);
+    const int64_t margin_blocks = (int64_t)n_grad * per;
+    if (grid + margin_blocks > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((mix_csr_margin_kernel<VEC, NT, MAP>), dim3((unsigned)(grid + margin_blocks)), dim3(kThreads), 0,
+                       (hipStream_t)stream, mix_dev, n_mix, d, n_chunks, grad_dev, B, per, loss, (int)margin_blocks);
+    return (int)hipGetLastError();
 }
 
 // target[col] += factor * c_m * val for the active rows (the sparse part of -eta g, or of g).
@@ -565,7 +614,7 @@ __global__ __launch_bounds__(kThreads) void scale_kernel(const HopGradJob* __res
                                                          int64_t d, float lambda, int64_t n_chunks) {
     int j;
     int64_t chunk;
-    if (!map_block(n_jobs, n_chunks, &j, &chunk)) return;
+    if (!map_block(blockIdx.x, n_jobs, n_chunks, &j, &chunk)) return;
     const HopGradJob* job = jobs + j;
     for (int q = 0; q < 4; ++q) {
         int64_t c = (chunk * 4 + q) * kThreads + threadIdx.x;
@@ -691,6 +740,15 @@ int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, voi
     hipLaunchKernelGGL(csr_margin_kernel, dim3((unsigned)(n_jobs * per)), dim3(kThreads), 0, (hipStream_t)stream,
                        jobs_dev, B, per, loss);
     return launch_status();
+}
+
+int hopk_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
+                        int loss, void* stream) {
+    if (n_grad <= 0 || B <= 0) return hopk_mix(mix_dev, n_mix, d, stream);
+    if (n_mix <= 0) return hopk_csr_margin(grad_dev, n_grad, B, loss, stream);
+    if ((d >> 2) >= (int64_t)1024 * kThreads * 4)
+        return launch_mix_csr_margin<4, 1, 14>(mix_dev, n_mix, d, grad_dev, n_grad, B, loss, stream);
+    return launch_mix_csr_margin<4, 1, 1>(mix_dev, n_mix, d, grad_dev, n_grad, B, loss, stream);
 }
 
 int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, int into_velocity, void* stream) {
