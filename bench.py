@@ -126,7 +126,7 @@ def run_config(cfgn, steps, warmup, graph, over=None):
             "ms_per_step": elapsed * 1e3 / steps,
             "config": {
                 "workload": c["name"] + (" (config %d of the synthetic suite)" % cfgn),
-                "N": c["N"], "d": c["d"], "s": c["s"], "b": c["b"], "iterations": c["K"],
+                "N": c["N"], "d": c["d"], "s": c["s"], "b": c["b"], "iterations": c["K"], "seed": c["seed"],
                 "step_records": n_step, "jump_records": n_jump, "waves": int(sched.n_waves),
                 "mean_A": float(A.mean()), "max_A": int(A.max()),
                 "step_definition": "one pass of hop_step over the whole schedule",
@@ -151,6 +151,7 @@ def main():
     ap.add_argument("--d", type=int, default=0, help="override the parameter count (not a valid bench line)")
     ap.add_argument("--momentum", type=float, default=0.0, help="per-worker momentum (not the default bench line)")
     ap.add_argument("--log-loss", action="store_true", help="log loss instead of hinge (SVM configs)")
+    ap.add_argument("--seed", type=int, default=0, help="seed of graph, slow set, delays and data (default: the suite's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the brief runs of the other configs")
     ap.add_argument("--graph", action="store_true",
@@ -180,6 +181,8 @@ def main():
         over["momentum"] = args.momentum
     if args.log_loss:
         over["loss"] = 1
+    if args.seed:
+        over["seed"] = args.seed
     res, c, p0 = run_config(args.config, args.steps, args.warmup, args.graph, over or None)
     mix = res["mix"]
     out = {
