@@ -188,6 +188,7 @@ size_t hop_arena_bytes(int32_t N, int64_t d, int32_t s, const hop_opts* o);
  * simulator works, anything touching the GPU returns HOP_ERR_NO_DEVICE. */
 int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64_t d, int32_t s,
              int32_t b, const hop_opts* opts, const hop_device* dev);
+/* Frees the context; waits for nothing: synchronise the stream first if kernels may still be running. */
 int hop_destroy(hop_ctx* ctx);
 
 /* x_{0,i} = p_0 (update-queue figure, line "Initialize local model parameters").  per_worker 0: p0
@@ -216,7 +217,8 @@ int hop_set_grad_source(hop_ctx* ctx, int mode, float variance, const float* ext
  * (also when the result is HOP_ERR_DEADLOCK).  Touches no device memory. */
 int hop_simulate(hop_ctx* ctx, const hop_delay_model* delays, int32_t max_iter, hop_schedule** out);
 int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* out);
-/* Frees a schedule and its device-side descriptors; do this before hop_destroy of its context. */
+/* Frees a schedule and its device-side descriptors.  A schedule may outlive its context (its host
+ * arrays stay valid), but hop_step refuses it once the context is gone. */
 int hop_schedule_free(hop_schedule* s);
 
 /* Enqueues waves [wave_begin, wave_end) of the schedule: per wave the gradient kernels of its STEP

@@ -28,12 +28,11 @@ def build_library():
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
     objs = []
-    tune = ["-DHOP_TUNE"] if os.environ.get("HOP_TUNE") else []      # kernel-variant sweeps only
     for src, extra in (("hop_kernels.hip", DEVICE),
                        ("hop_api.cpp", []),
                        ("hop_sim.cpp", ["-ffp-contract=off"])):
         o = os.path.join(OBJ, src + ".o")
-        _run([hipcc] + COMMON + extra + tune + ["-c", os.path.join(CSRC, src), "-o", o])
+        _run([hipcc] + COMMON + extra + ["-c", os.path.join(CSRC, src), "-o", o])
         objs.append(o)
     _run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950"] + objs + ["-o", LIB])
     return LIB

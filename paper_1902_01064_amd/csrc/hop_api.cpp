@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <new>
 
 #include "hop_internal.h"
@@ -36,9 +37,6 @@ int ring_depth(int s, int max_ig, uint32_t max_latency) {
 // Every slot starts on a 256-byte boundary; the extra 256 bytes keep the slots of a power-of-two d
 // from all mapping to the same HBM channel phase.
 int64_t slot_stride(int64_t d) {
-#ifdef HOP_TUNE
-    if (const char* e = getenv("HOP_PAD_FLOATS")) return round_up(d, kAlignFloats) + atoll(e);
-#endif
     return round_up(d, kAlignFloats) + kAlignFloats;
 }
 
@@ -297,8 +295,20 @@ size_t hop_arena_bytes(int32_t N, int64_t d, int32_t s, const hop_opts* o) {
     return (size_t)floats * sizeof(float);
 }
 
+static int init_ctx(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64_t d, int32_t s, int32_t b,
+                    const hop_opts* opts, const hop_device* dev);
+
 int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64_t d, int32_t s, int32_t b,
              const hop_opts* opts, const hop_device* dev) {
+    try {
+        return init_ctx(out, g, W, N, d, s, b, opts, dev);
+    } catch (const std::bad_alloc&) {
+        return HOP_ERR_NOMEM;
+    }
+}
+
+static int init_ctx(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64_t d, int32_t s, int32_t b,
+                    const hop_opts* opts, const hop_device* dev) {
     if (!out) return HOP_ERR_INVALID_ARG;
     *out = nullptr;
     if (!g || !W || !g->row_ptr || N < 1 || d < 1 || d > 0xFFFFFFFFll || s < 0 || b < 0 || g->N != N)
@@ -310,7 +320,8 @@ int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64
     if (o.max_ig < 0 || o.max_skip < 1 || o.trigger < 0 || o.batch < 0 || o.batch > kMaxBatch ||
         (o.loss != HOP_LOSS_HINGE && o.loss != HOP_LOSS_LOG) || !(o.momentum >= 0.f && o.momentum < 1.f))
         return HOP_ERR_INVALID_ARG;
-    hop_ctx* c = new (std::nothrow) hop_ctx();
+    std::unique_ptr<hop_ctx> holder(new (std::nothrow) hop_ctx());
+    hop_ctx* c = holder.get();
     if (!c) return HOP_ERR_NOMEM;
     c->N = N; c->d = d; c->s = s; c->b = b; c->opts = o;
     c->max_ig = effective_max_ig(s, &o);
@@ -364,18 +375,16 @@ int hop_init(hop_ctx** out, const hop_graph* g, const float* W, int32_t N, int64
             c->vel = o.momentum > 0.f ? c->partial + (int64_t)N * partial_floats(d, o.batch) : nullptr;
         }
     }
-    if (rc != HOP_OK) {
-        delete c;
-        return rc;
-    }
+    if (rc != HOP_OK) return rc;
     c->data.assign(N, HopData{});
     c->version.assign(N, 0);
-    *out = c;
+    *out = holder.release();
     return HOP_OK;
 }
 
 int hop_destroy(hop_ctx* c) {
     if (!c) return HOP_ERR_INVALID_ARG;
+    for (hop_schedule* s : c->schedules) s->owner = nullptr;   // they outlive the context as host data only
     for (void* e : c->prof.ev) (void)hipEventDestroy((hipEvent_t)e);
     if (c->capture_stream) (void)hipStreamDestroy((hipStream_t)c->capture_stream);
     delete c;
@@ -485,6 +494,12 @@ int hop_simulate(hop_ctx* c, const hop_delay_model* dm, int32_t max_iter, hop_sc
         delete s;
         return rc;
     }
+    try {
+        c->schedules.push_back(s);
+    } catch (const std::bad_alloc&) {
+        delete s;
+        return HOP_ERR_NOMEM;
+    }
     s->owner = c;
     *out = s;
     return rc;
@@ -523,9 +538,12 @@ int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* v) {
 
 int hop_schedule_free(hop_schedule* s) {
     if (!s) return HOP_ERR_INVALID_ARG;
-    if (s->owner && s->owner->running == s) {
-        s->owner->running = nullptr;
-        s->owner->next_wave = 0;
+    if (hop_ctx* c = s->owner) {
+        if (c->running == s) {
+            c->running = nullptr;
+            c->next_wave = 0;
+        }
+        c->schedules.erase(std::remove(c->schedules.begin(), c->schedules.end(), s), c->schedules.end());
     }
     free_device_side(s);
     delete s;
@@ -610,7 +628,12 @@ int hop_step(hop_ctx* c, const hop_schedule* sched, int32_t wave_begin, int32_t 
     if (wave_begin < 0 || wave_begin > wave_end || wave_end > s->n_waves) return HOP_ERR_INVALID_ARG;
     if (wave_begin != 0 && (c->running != s || wave_begin != c->next_wave)) return HOP_ERR_STATE;
     if (s->built_mode != c->grad_mode || s->built_epoch != c->epoch) {
-        int rc = build_jobs(c, s);
+        int rc;
+        try {
+            rc = build_jobs(c, s);
+        } catch (const std::bad_alloc&) {
+            rc = HOP_ERR_NOMEM;
+        }
         if (rc != HOP_OK) return rc;
     }
     c->running = s;
@@ -712,27 +735,7 @@ int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* stream) {
     HOP_HIP(nullptr, hipMalloc((void**)&dev, host.size() * sizeof(HopMixJob)));
     hipError_t e = hipMemcpy(dev, host.data(), host.size() * sizeof(HopMixJob), hipMemcpyHostToDevice);
     int rc = 0;
-#ifdef HOP_TUNE
-    // tuning builds only: run the launch three times and print the last one's duration
-    hipEvent_t t0, t1;
-    (void)hipEventCreate(&t0);
-    (void)hipEventCreate(&t1);
-    if (e == hipSuccess) {
-        (void)hopk_mix(dev, n_jobs, d, stream);
-        (void)hopk_mix(dev, n_jobs, d, stream);
-        (void)hipEventRecord(t0, (hipStream_t)stream);
-    }
-#endif
     if (e == hipSuccess) rc = hopk_mix(dev, n_jobs, d, stream);
-#ifdef HOP_TUNE
-    (void)hipEventRecord(t1, (hipStream_t)stream);
-    (void)hipEventSynchronize(t1);
-    float tune_ms = 0.f;
-    (void)hipEventElapsedTime(&tune_ms, t0, t1);
-    std::fprintf(stderr, "HOP_TUNE mix_ms %.4f\n", tune_ms);
-    (void)hipEventDestroy(t0);
-    (void)hipEventDestroy(t1);
-#endif
     hipError_t e2 = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(dev);
     if (e != hipSuccess) return hip_fail(nullptr, e, "hipMemcpy");

@@ -128,6 +128,7 @@ struct hop_ctx {
     const float* external = nullptr;
     uint64_t epoch = 0;                 // bumped whenever job descriptors would change
     std::vector<int32_t> version;       // newest iteration held per worker
+    std::vector<hop_schedule*> schedules;   // live schedules of this context (hop_simulate .. hop_schedule_free)
     const hop_schedule* running = nullptr;
     int next_wave = 0;
     bool profiling = false;

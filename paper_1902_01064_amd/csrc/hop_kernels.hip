@@ -52,11 +52,11 @@ inline int64_t grid_for(int n_jobs, int64_t n_chunks) {
 // weights from Eq. 2 times the mixing matrix, already normalised on the host).
 //
 // Template knobs: VEC float4 per thread per source; NT 0 = ordinary accesses, 1 = g and the result
-// non-temporal (each touched once), 2 = sources too; MAP 0 = job-major blocks, 1 = the XCD-aware map
-// above, 2 = chunk-major without regard to XCDs, 3 = one contiguous eighth of the columns per XCD,
-// 10 + G = XCD-aware with runs of G consecutive chunks per XCD; T threads per workgroup.
-// Measured on 32 jobs x 25 M columns with ~7.6 shared sources each: MAP 1 is 2.3x faster than MAP 0 and
-// 1.45x faster than MAP 2; vector width, block size and cache hints move the time by under 5 %.
+// non-temporal (each touched once), 2 = sources too; MAP 1 = the XCD-aware map above, 10 + G = the same
+// with runs of G consecutive chunks per XCD; T threads per workgroup.
+// Measured on 32 jobs x 25 M columns with ~7.6 shared sources each: job-major workgroups are 2.3x slower than
+// MAP 1 and chunk-major ones that ignore the XCDs 1.45x slower; vector width (1-8), block size (128-1024) and
+// cache hints move the time by under 5 %.
 template <int NT>
 __device__ __forceinline__ float4 ld_src(const float* p, int64_t i) {
     return NT >= 2 ? ld4_stream(p, i) : ld4(p, i);
@@ -194,33 +194,18 @@ __device__ __forceinline__ void mix_block(const HopMixJob* __restrict__ jobs, in
     int64_t chunk;
     if (MAP == 1) {
         if (!map_block(bid, n_jobs, n_chunks, &j, &chunk)) return;
-    } else if (MAP == 0) {
-        j = (int)(bid / n_chunks);
-        chunk = bid % n_chunks;
-    } else if (MAP >= 10) {
+    } else {
         // XCD-aware like MAP 1, but every XCD owns runs of G = MAP - 10 consecutive chunks, and visits
         // them job by job: longer contiguous pieces of every stream are in flight at a time
-        constexpr int G = MAP - 10;
-        int64_t b = bid;
-        int xcd = (int)(b % kXcd);
-        int64_t local = b / kXcd;
+        static_assert(MAP == 1 || MAP > 10, "MAP is 1 or 10 + run length");
+        constexpr int G = MAP > 10 ? MAP - 10 : 1;
+        int xcd = (int)(bid % kXcd);
+        int64_t local = bid / kXcd;
         int sub = (int)(local % G);
         j = (int)((local / G) % n_jobs);
         int64_t group = local / ((int64_t)G * n_jobs);
         chunk = (group * kXcd + xcd) * G + sub;
         if (chunk >= n_chunks) return;
-    } else if (MAP == 3) {
-        // every XCD owns one contiguous eighth of the columns
-        int64_t b = bid;
-        int xcd = (int)(b % kXcd);
-        int64_t local = b / kXcd;
-        int64_t per_xcd = (n_chunks + kXcd - 1) / kXcd;
-        j = (int)(local % n_jobs);
-        chunk = xcd * per_xcd + local / n_jobs;
-        if (local / n_jobs >= per_xcd || chunk >= n_chunks) return;
-    } else {
-        j = (int)(bid % n_jobs);
-        chunk = bid / n_jobs;
     }
     const HopMixJob* job = jobs + j;
     const int64_t n4 = d >> 2;
@@ -289,8 +274,8 @@ int64_t mix_grid(int n_jobs, int64_t d, int64_t* n_chunks_out) {
     int64_t per = (int64_t)T * VEC;
     int64_t n_chunks = (n4 + per - 1) / per;
     if (n_chunks < 1) n_chunks = 1;
-    int64_t grid = (MAP == 1 || MAP == 3) ? grid_for(n_jobs, n_chunks) : n_chunks * n_jobs;
-    if (MAP >= 10) {
+    int64_t grid = grid_for(n_jobs, n_chunks);
+    if (MAP > 10) {
         int64_t span = (int64_t)kXcd * (MAP - 10);
         grid = (n_chunks + span - 1) / span * span * n_jobs;
     }
@@ -651,43 +636,6 @@ inline int launch_status() { return (int)hipGetLastError(); }
 
 int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
     if (n_jobs <= 0) return 0;
-#ifdef HOP_TUNE
-    // tuning builds only: pick a variant by HOP_MIX_VARIANT (never compiled into the product)
-    static const int variant = getenv("HOP_MIX_VARIANT") ? atoi(getenv("HOP_MIX_VARIANT")) : 0;
-    switch (variant) {
-        case 1: return launch_mix<2, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
-        case 2: return launch_mix<8, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
-        case 3: return launch_mix<1, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
-        case 4: return launch_mix<4, 0, 1, 256>(jobs_dev, n_jobs, d, stream);
-        case 5: return launch_mix<4, 2, 1, 256>(jobs_dev, n_jobs, d, stream);
-        case 6: return launch_mix<4, 1, 0, 256>(jobs_dev, n_jobs, d, stream);
-        case 7: return launch_mix<4, 1, 2, 256>(jobs_dev, n_jobs, d, stream);
-        case 8: return launch_mix<2, 1, 1, 512>(jobs_dev, n_jobs, d, stream);
-        case 9: return launch_mix<4, 1, 1, 512>(jobs_dev, n_jobs, d, stream);
-        case 10: return launch_mix<1, 1, 1, 1024>(jobs_dev, n_jobs, d, stream);
-        case 11: return launch_mix<2, 0, 1, 256>(jobs_dev, n_jobs, d, stream);
-        case 12: return launch_mix<2, 1, 1, 128>(jobs_dev, n_jobs, d, stream);
-        case 13: return launch_mix<4, 1, 1, 128>(jobs_dev, n_jobs, d, stream);
-        case 14: return launch_mix<1, 1, 1, 512>(jobs_dev, n_jobs, d, stream);
-        case 15: return launch_mix<4, 1, 3, 256>(jobs_dev, n_jobs, d, stream);
-        case 16: return launch_mix<2, 1, 3, 256>(jobs_dev, n_jobs, d, stream);
-        case 17: return launch_mix<4, 0, 0, 256>(jobs_dev, n_jobs, d, stream);
-        case 18: return launch_mix<1, 0, 0, 256>(jobs_dev, n_jobs, d, stream);
-        case 19: return launch_mix<2, 0, 0, 256>(jobs_dev, n_jobs, d, stream);
-        case 20: return launch_mix<1, 1, 0, 256>(jobs_dev, n_jobs, d, stream);
-        case 21: return launch_mix<1, 0, 0, 512>(jobs_dev, n_jobs, d, stream);
-        case 22: return launch_mix<1, 0, 0, 1024>(jobs_dev, n_jobs, d, stream);
-        case 30: return launch_mix<4, 1, 12, 256>(jobs_dev, n_jobs, d, stream);
-        case 31: return launch_mix<4, 1, 14, 256>(jobs_dev, n_jobs, d, stream);
-        case 32: return launch_mix<4, 1, 18, 256>(jobs_dev, n_jobs, d, stream);
-        case 33: return launch_mix<2, 1, 14, 256>(jobs_dev, n_jobs, d, stream);
-        case 34: return launch_mix<2, 1, 18, 256>(jobs_dev, n_jobs, d, stream);
-        case 35: return launch_mix<1, 1, 18, 256>(jobs_dev, n_jobs, d, stream);
-        case 36: return launch_mix<1, 1, 26, 256>(jobs_dev, n_jobs, d, stream);
-        case 37: return launch_mix<2, 1, 26, 256>(jobs_dev, n_jobs, d, stream);
-        default: break;
-    }
-#endif
     // long vectors: every XCD takes runs of 4 consecutive 16 KB chunks (3-4 % faster on 64-100 MB
     // vectors: longer contiguous pieces per stream); short ones: single chunks, less padding
     if ((d >> 2) >= (int64_t)1024 * kThreads * 4) return launch_mix<4, 1, 14, 256>(jobs_dev, n_jobs, d, stream);

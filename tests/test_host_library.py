@@ -168,3 +168,17 @@ def test_argument_checking():
     assert need >= 4 * (2 + 1) * 8 * 4
     sched.free()
     hop.hop_destroy(ctx)
+
+
+def test_schedule_may_outlive_its_context():
+    """A schedule is host data: freeing it after hop_destroy of its context must be harmless, and
+    several schedules of one context can be freed in any order."""
+    c = inputs.config(1)
+    ctx = host_ctx(c)
+    a = hop.hop_simulate(ctx, 5, c["delay_kind"], c["mult"])
+    b = hop.hop_simulate(ctx, 7, c["delay_kind"], c["mult"])
+    keep = list(b.iter)
+    a.free()
+    hop.hop_destroy(ctx)
+    assert list(b.iter) == keep and b.n_records == 4 * 7
+    b.free()
