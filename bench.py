@@ -128,7 +128,9 @@ def run_config(cfgn, steps, warmup, graph, over=None):
                 "workload": c["name"] + (" (config %d of the synthetic suite)" % cfgn),
                 "N": c["N"], "d": c["d"], "s": c["s"], "b": c["b"], "iterations": c["K"], "seed": c["seed"],
                 "step_records": n_step, "jump_records": n_jump, "waves": int(sched.n_waves),
-                "mean_A": float(A.mean()), "max_A": int(A.max()),
+                "mean_A": float(A.mean()), "min_A": int(A.min()), "max_A": int(A.max()),
+                "records_per_wave": float(len(A)) / max(int(sched.n_waves), 1),
+                "simulated_makespan_units": float(max(sched.finish_time)) / float(1 << 20),
                 "step_definition": "one pass of hop_step over the whole schedule",
                 "launch": "hip graph replay" if graph else "kernel by kernel",
             },
