@@ -204,7 +204,7 @@ def main():
         "roofline": {
             "bound": "hbm", "kernel": "mix_kernel", "achieved": mix["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": mix["GBps"] / HBM_PEAK_GBS,
-            "traffic": read_traffic("hop_mix_cfg%d_traffic.txt" % args.config),
+            "traffic": None if over else read_traffic("hop_mix_cfg%d_traffic.txt" % args.config),
             "launches": mix["launches"], "avg_launch_us": mix["ms"] * 1e3 / max(mix["launches"], 1),
             "algorithmic_bytes_per_launch": mix["bytes"] / max(mix["launches"], 1),
         },
