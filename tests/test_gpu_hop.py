@@ -551,3 +551,43 @@ def test_vector_longer_than_2_to_31_elements():
         assert worst <= STEP_TOL * 3
     finally:
         sess.close()
+
+
+def random_mode(rnd, case):
+    """One seeded draw over graphs (directed and asymmetric ones included), staleness, backup
+    workers, token bounds, skipping, delays, latencies, models, losses, momentum and ragged sizes."""
+    nb = rnd.choice([lambda: inputs.ring(rnd.choice([3, 5, 8])), lambda: inputs.torus(3, 3),
+                     lambda: inputs.complete(rnd.choice([2, 4, 6])),
+                     lambda: inputs.ring_with_chords(12, 1, rnd.randrange(100)),
+                     lambda: inputs.directed_cycle([0, 3, 1, 4, 2]), lambda: inputs.ring_based(8),
+                     lambda: inputs.double_ring(8)])()
+    N = len(nb)
+    s = rnd.choice([0, 1, 2, 4])
+    b = rnd.randrange(0, min(len(l) for l in nb))
+    model = rnd.choice(["dense", "csr", "synth", "synth"])
+    # (d = 1 is the degenerate-shape test's: with a single entry the metric has no rms floor, and the fp32
+    # sum of a 200-sample gradient alone can leave 1.6e-5 of an entry that happens to be small)
+    d = rnd.choice([6, 64, 1000, 4099, 8192 + rnd.randrange(4), 20000 + rnd.randrange(8)])
+    symmetric = all(i in nb[j] for i in range(N) for j in nb[i])
+    weights = rnd.choice([inputs.uniform_weights, inputs.metropolis_weights]) if symmetric else inputs.uniform_weights
+    c = dict(name="random mode %d" % case, in_nbrs=nb, W=weights(nb), N=N, d=max(d, 600) if model == "csr" else d,
+             s=s, b=b, max_ig=rnd.choice([0, 0, 1, 3, 6]), skip_on=rnd.random() < 0.5, max_skip=rnd.choice([2, 10]),
+             trigger=rnd.choice([0, 1, 2]), lr=rnd.choice([0.01, 0.1]), lam=rnd.choice([0.0, 1e-4, 1e-2]),
+             seed=1000 + case, delay_kind=rnd.choice([0, 1, 2]), mult=[rnd.choice([1.0, 1.0, 2.0, 3.5]) for _ in nb],
+             K=rnd.choice([1, 7, 16]), model=model, momentum=rnd.choice([0.0, 0.0, 0.9, 0.5]), loss=rnd.choice([0, 0, 1]),
+             max_latency=rnd.choice([1, 1, 1 << 19, 3 << 20]) if s >= 1 else 1, rows=0, batch=0, grad_var=1e-3)
+    if model == "dense":
+        c.update(rows=rnd.choice([7, 300]), batch=rnd.choice([1, 5, 64, 200]))
+    elif model == "csr":
+        c.update(rows=rnd.choice([50, 400]), batch=rnd.choice([1, 16, 100]), nnz=rnd.choice([1, 8, 40]), zipf_a=1.1)
+    return c
+
+
+def test_random_modes():
+    """48 seeded random combinations of everything the library takes, each through the whole-run and
+    the per-record check."""
+    import random
+    rnd = random.Random(5)
+    for case in range(48):
+        c = random_mode(rnd, case)
+        run_parity(c)
