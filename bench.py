@@ -210,6 +210,11 @@ def main():
         },
         "kernels": {k: {kk: vv for kk, vv in res[k].items() if kk != "bytes"} for k in ("mix", "grad", "synth")},
     }
+    r = out["roofline"]
+    if r["traffic"] and r["avg_launch_us"] > 0:
+        # the same launches seen from the HBM side: counter bytes over the measured duration
+        r["traffic_GBps"] = r["traffic"] / (r["avg_launch_us"] * 1e-6) / 1e9
+        r["traffic_frac"] = r["traffic_GBps"] / HBM_PEAK_GBS
     if not args.no_cpu_baseline:
         from oracle import protocol
         if c["model"] == "synth" and not args.momentum:
