@@ -213,8 +213,10 @@ int hop_set_data_csr(hop_ctx* ctx, int32_t worker, const int64_t* rowptr, const 
  * HOP_GRAD_EXTERNAL only, device, N x d floats (worker-major), read whenever a STEP runs. */
 int hop_set_grad_source(hop_ctx* ctx, int mode, float variance, const float* external);
 
-/* Runs the protocol for max_iter iterations per worker on the host and returns the schedule
- * (also when the result is HOP_ERR_DEADLOCK).  Touches no device memory. */
+/* Runs the queue protocol (update and token queues, backup workers, bounded staleness, skipping:
+ * Sections 4.1 - 4.4 and 5) for max_iter iterations per worker on the host, on the compute delays of
+ * `delays` (NULL: one time unit each), and returns the schedule (also when the result is
+ * HOP_ERR_DEADLOCK).  Touches no device memory. */
 int hop_simulate(hop_ctx* ctx, const hop_delay_model* delays, int32_t max_iter, hop_schedule** out);
 int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* out);
 /* Frees a schedule and its device-side descriptors.  A schedule may outlive its context (its host
@@ -222,7 +224,9 @@ int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* out);
 int hop_schedule_free(hop_schedule* s);
 
 /* Enqueues waves [wave_begin, wave_end) of the schedule: per wave the gradient kernels of its STEP
- * records, then one fused Reduce + Apply launch over all its records.  Records of one wave touch no
+ * records (Compute on x_k, Section 3.2), then one fused Reduce + Apply launch over all its records
+ * (with CSR data the margins ride in that launch and the sparse part of the gradient is scattered
+ * into the results right after it).  Records of one wave touch no
  * ring slot in a conflicting way, so the result equals running the records one by one in schedule
  * order.  Waves must be run in order starting from 0 after hop_set_params (or continue where the last
  * call stopped); wave_end = -1 means "to the end".  A finished schedule may be started again from
