@@ -379,3 +379,53 @@ def test_backup_example_state_of_the_figure():
             states.add(tuple(it))
             assert it[2] - it[1] <= 1 and it[0] == 0
     assert (0, 3, 4) in states
+
+
+def test_gap_table_from_the_trace_with_library_distances():
+    """Table of iteration-gap bounds, judged outside the oracle: Iter(i) is rebuilt from the trace's
+    "enter" events and path lengths come from scipy, so neither the oracle's own assertions nor its
+    shortest-path code take part.  Rows: standard min(len(j->i), max_ig len(i->j)) - with max_ig = 2
+    the same figures as the NOTIFY-ACK row -, bounded staleness (s+1) len(j->i), backup workers
+    only the token side.  A frozen worker drives the others to the bound, which must be attained."""
+    from scipy.sparse import csr_matrix
+    from scipy.sparse.csgraph import shortest_path
+
+    graphs = [inputs.directed_cycle([0, 2, 4, 1, 3]), inputs.ring(6), inputs.torus(3, 3), inputs.ring_with_chords(12, 1, 2)]
+    attained = 0
+    for gi, nb in enumerate(graphs):
+        N = len(nb)
+        adj = np.zeros((N, N))
+        for i, lst in enumerate(nb):
+            for j in lst:
+                adj[j, i] = 1                              # edge j -> i: j sends to i
+        dist = shortest_path(csr_matrix(adj), method="D", directed=True, unweighted=True)   # dist[a, b]: a -> b
+        mindeg = min(len(l) for l in nb)
+        for s, b, ig in [(0, 0, 1), (0, 0, 2), (0, 0, 3), (1, 0, 4), (3, 0, 2), (0, 1, 2), (2, 1, 3)]:
+            if b >= mindeg:
+                continue
+            for frozen in (None, 0):
+                mult = [1.0 + 0.5 * ((3 * i + gi) % 4) for i in range(N)]
+                if frozen is not None:
+                    mult[frozen] = NEVER
+                h = protocol.Hop(nb, inputs.uniform_weights(nb), s, b, 25, max_ig=ig, seed=gi, delay_kind=rng.DELAY_EXP1,
+                                 mult=mult, check=False, trace=True)
+                h.run()
+                it = [0] * N
+                worst = np.zeros((N, N))
+                for ev in h.trace:
+                    if ev[0] != "enter":
+                        continue
+                    it[ev[1]] = ev[2]
+                    for j in range(N):
+                        worst[ev[1], j] = max(worst[ev[1], j], it[ev[1]] - it[j])
+                for i in range(N):
+                    for j in range(N):
+                        if i == j:
+                            continue
+                        bound = h.max_ig * dist[i, j]                       # token side: len(i -> j)
+                        if b == 0:
+                            bound = min(bound, (s + 1 if s >= 1 else 1) * dist[j, i])
+                        assert worst[i, j] <= bound, (gi, s, b, ig, frozen, i, j, worst[i, j], bound)
+                        if frozen == j and worst[i, j] == bound:
+                            attained += 1
+    assert attained > 20
