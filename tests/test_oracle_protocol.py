@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from conftest import golden
-from oracle import brute, protocol, rng, waves
+from oracle import arith, brute, protocol, rng, waves
 from oracle.arith import reduce_weights
 from paper_1902_01064_amd import inputs
 
@@ -429,3 +429,69 @@ def test_gap_table_from_the_trace_with_library_distances():
                         if frozen == j and worst[i, j] == bound:
                             attained += 1
     assert attained > 20
+
+
+def test_weight_index_is_sender_then_receiver_on_a_directed_graph():
+    """Section 3.1 puts W_ij on what worker i sends to worker j.  A directed 3-cycle with a different
+    self weight per node makes the two index orders differ: node i keeps a_i of its own value and
+    takes 1 - a_i from its only in-neighbour.  One lock-step iteration by hand, then the oracle."""
+    nb = inputs.directed_cycle([0, 1, 2])                 # 0 -> 1 -> 2 -> 0
+    keep = [0.9, 0.5, 0.2]
+    W = np.zeros((3, 3))
+    for i in range(3):
+        (j,) = nb[i]
+        W[i][i] = keep[i]                                 # sender i, receiver i
+        W[j][i] = 1.0 - keep[i]                           # sender j, receiver i
+    assert not np.allclose(W, W.T)
+    x0 = np.array([[1.0], [10.0], [100.0]], dtype=np.float32)
+    h = protocol.Hop(nb, W, 0, 0, 1, check=True)
+    recs = h.run()
+    rings = arith.init_rings(x0, 3, h.D)
+    ver = arith.execute(recs, rings, arith.GradZero(), 0.1)
+    got = np.array(arith.final_params(rings, ver)).ravel()
+    by_hand = [keep[i] * x0[i, 0] + (1.0 - keep[i]) * x0[nb[i][0], 0] for i in range(3)]
+    assert np.allclose(got, by_hand, rtol=1e-6)
+    w64, _ = reduce_weights(W, 1, 0, 0, [1, nb[1][0]], [0, 0])
+    assert np.allclose(w64, [0.5, 0.5]) and np.allclose(reduce_weights(W, 0, 0, 0, [0, nb[0][0]], [0, 0])[0], [0.9, 0.1])
+
+
+def test_stale_updates_are_dropped_at_dequeue():
+    """Section 6.2 (a): with a backup worker the slow neighbour's updates arrive after their iteration
+    has been reduced, and every dequeue throws away what is not newer than the iteration it serves.
+    The test keeps its own queues from the trace (deliveries in, everything <= k out at Recv(k)) and
+    the oracle must end with exactly the same contents."""
+    nb = inputs.complete(4)
+    h = protocol.Hop(nb, inputs.uniform_weights(nb), 0, 1, 30, max_ig=3, delay_kind=rng.DELAY_EXP1,
+                     mult=[3.0, 1.0, 1.0, 1.0], seed=4, check=True, trace=True)
+    h.run()
+    assert not h.stalled and h.late_sends > 0             # the slow worker really sent into the past
+    mine = {edge: [] for edge in h.queue}
+    dropped = 0
+    for item in h.trace:
+        if item[0] == "deliver":
+            _, snd, rcv, tag = item
+            mine[(snd, rcv)].append(tag)
+        elif item[0] == "recv":
+            _, i, k, _ = item
+            for j in nb[i]:
+                dropped += sum(1 for t in mine[(j, i)] if t < k)
+                mine[(j, i)] = [t for t in mine[(j, i)] if t > k]
+    assert dropped > 0
+    for edge in mine:
+        assert sorted(mine[edge]) == sorted(h.queue[edge]), edge
+
+
+def test_skip_trigger_is_a_strict_threshold():
+    """hop_opts.trigger: a worker jumps only if it is MORE than `trigger` iterations behind.  Section
+    5's example (a) - staleness 4, B and C exactly 4 ahead of A when A's slow iteration ends - with
+    trigger 4 must not jump, with trigger 3 must."""
+    K, unit = 30, rng.TICKS_PER_UNIT
+    table = np.full((3, K), unit, dtype=np.uint64)
+    table[0, 5:] = 1000 * unit
+    jumps = {}
+    for trig in (3, 4):
+        h = protocol.Hop(inputs.complete(3), inputs.uniform_weights(inputs.complete(3)), 4, 0, K, skip_on=True,
+                         max_skip=10, trigger=trig, delay_kind=rng.DELAY_TABLE, table=table, check=True)
+        h.run()
+        jumps[trig] = h.n_jumps
+    assert jumps[4] == 0 and jumps[3] > 0
