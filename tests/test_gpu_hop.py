@@ -591,3 +591,18 @@ def test_random_modes():
     for case in range(48):
         c = random_mode(rnd, case)
         run_parity(c)
+
+
+@pytest.mark.parametrize("model", ["csr", "dense", "synth"])
+def test_records_wider_than_the_unrolled_kernels_with_momentum(model):
+    """A complete graph of 14 workers gives records of 14 terms, past the 12 the mix kernel unrolls, on
+    a ragged d; with momentum, and for CSR data with lambda w folded into the velocity inside the mix."""
+    nb = inputs.complete(14)
+    c = dict(inputs.config(3 if model == "csr" else 1, d=4099, rows=256, K=6), in_nbrs=nb, W=inputs.uniform_weights(nb),
+             N=14, s=1, b=0, skip_on=False, mult=None, momentum=0.9, lam=1e-2, model=model, grad_var=1e-3,
+             name="wide records, " + model)
+    if model == "synth":
+        c.update(batch=0, rows=0)
+    elif model == "dense":
+        c.update(batch=32)
+    run_parity(c)

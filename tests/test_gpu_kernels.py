@@ -194,3 +194,36 @@ def test_copy_and_download():
     torch.cuda.synchronize()
     assert torch.equal(a, b)
     assert np.array_equal(hop.hop_download(a.data_ptr() + 40, 10, stream()), np.arange(10, 20, dtype=np.float32))
+
+
+def test_mix_with_velocity_for_every_width():
+    """Momentum inside the fused kernel (v <- mu v + g in place, Apply with the new v) for the unrolled
+    widths, the looped ones (A > 12) and the ragged tail, with and without a gradient."""
+    d = 4099
+    rs = np.random.default_rng(11)
+    base = rs.normal(size=d)
+    host = [(base + 0.05 * rs.normal(size=d)).astype(np.float32) for _ in range(24)]
+    pool = [aligned(d) for _ in host]
+    for t, h in zip(pool, host):
+        t.copy_(torch.from_numpy(h))
+    jobs, keep, want = [], [], []
+    for A in (1, 2, 4, 7, 12, 13, 20):
+        for use_g in (True, False):
+            pick = rs.choice(len(host), size=A, replace=False)
+            w = rs.dirichlet(np.ones(A)).astype(np.float32)
+            gh = (0.03 * rs.normal(size=d)).astype(np.float32)
+            vh = (0.1 * rs.normal(size=d)).astype(np.float32)
+            g, vel, out = aligned(d), aligned(d), aligned(d)
+            g.copy_(torch.from_numpy(gh))
+            vel.copy_(torch.from_numpy(vh))
+            out.fill_(float("nan"))
+            keep += [g, vel, out]
+            jobs.append(dict(out=out.data_ptr(), g=g.data_ptr() if use_g else None, eta=0.05, vel=vel.data_ptr(), mu=0.9,
+                             src=[pool[p].data_ptr() for p in pick], w=list(w)))
+            v64, v32 = arith.momentum_step(vh, gh if use_g else None, 0.9)
+            want.append((out, vel, arith.reduce_apply([host[p] for p in pick], w, v64, 0.05), v32))
+    hop.hop_mix(jobs, d, stream())
+    torch.cuda.synchronize()
+    for out, vel, ref, vref in want:
+        assert rel_err(out.cpu().numpy(), ref) <= 1e-5
+        assert rel_err(vel.cpu().numpy(), vref) <= 1e-6
