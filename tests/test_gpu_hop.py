@@ -606,3 +606,17 @@ def test_records_wider_than_the_unrolled_kernels_with_momentum(model):
     elif model == "dense":
         c.update(batch=32)
     run_parity(c)
+
+
+@pytest.mark.parametrize("r,s,b,skip,model", [(12, 0, 0, False, "synth"), (16, 2, 1, True, "synth"), (10, 3, 2, True, "csr")])
+def test_many_workers(r, s, b, skip, model):
+    """Tori of 144, 256 and 100 workers: waves of more than a hundred records in one launch, hybrid
+    mode with jumps at that width, CSR scatters of a hundred records."""
+    nb = inputs.torus(r, r)
+    N = len(nb)
+    mult = [1.0 + 2.0 * ((7 * i) % 11 == 0) for i in range(N)]
+    c = dict(inputs.config(3 if model == "csr" else 4, d=2051, rows=128, K=12), in_nbrs=nb, W=inputs.uniform_weights(nb),
+             N=N, s=s, b=b, skip_on=skip, mult=mult, model=model, name="torus %dx%d %s" % (r, r, model), delay_kind=1)
+    if model == "csr":
+        c.update(batch=16, nnz=8)
+    run_parity(c, per_wave_check=(N <= 144))
