@@ -620,3 +620,36 @@ def test_many_workers(r, s, b, skip, model):
     if model == "csr":
         c.update(batch=16, nnz=8)
     run_parity(c, per_wave_check=(N <= 144))
+
+
+def test_training_learns_the_hidden_separator_without_the_oracle():
+    """End to end and independent of the oracle: 16 workers with a straggler, staleness, skipping and
+    Exp(1) delays train the linear SVM on their own shards of labels from one hidden w*.  Every
+    replica must end up classifying fresh samples far above chance, point along w*, and agree with the
+    others much more closely than with the starting point."""
+    c = inputs.config(2, d=2048, rows=2048, K=300, lr=0.1)
+    p0, data = make_data(c)
+    sess = Session(c)
+    try:
+        attach(sess, c, p0, data)
+        sess.simulate()
+        sess.step()
+        sess.sync()
+        got, its = sess.params()
+        assert its == [300] * 16
+        X = torch.stack([g.clone() for g in got])                                   # [16, d] on the GPU
+    finally:
+        sess.close()
+    ws = inputs.hidden_w(c["seed"], c["d"]).to(X.device)          # the CPU stream make_data drew the labels from
+    gen = torch.Generator(device=X.device).manual_seed(99)
+    fresh = torch.randn(8192, c["d"], generator=gen, device=X.device)
+    y = torch.sign(fresh @ ws)
+    acc = ((fresh @ X.T).sign() == y[:, None]).float().mean(0)                      # per replica
+    acc0 = ((fresh @ p0.to(X.device)).sign() == y).float().mean()
+    cos = (X @ ws) / (X.norm(dim=1) * ws.norm())
+    spread = (X - X.mean(0)).norm(dim=1).max() / X.mean(0).norm()
+    print("  accuracy %.3f..%.3f (start %.3f)  cos(w, w*) %.3f..%.3f  spread %.3f"
+          % (acc.min(), acc.max(), acc0, cos.min(), cos.max(), spread), flush=True)
+    assert acc.min() > 0.85 and abs(float(acc0) - 0.5) < 0.1
+    assert cos.min() > 0.9
+    assert spread < 0.2
