@@ -17,6 +17,7 @@ namespace {
 constexpr int64_t kAlignFloats = 64;       // 256 bytes
 constexpr int kMaxBatch = 1024;
 constexpr size_t kMaxPendingEvents = 1 << 15;
+constexpr int64_t kDenseInPlaceBytes = 2 << 20;
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
@@ -99,6 +100,9 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
         HOP_HIP(c, hipMalloc((void**)&s->coef_dev, (size_t)R * B * sizeof(float)));
         HOP_HIP(c, hipMemset(s->coef_dev, 0, (size_t)R * B * sizeof(float)));
     }
+    // dense minibatches of up to 2 MB per record take the two-launch path of launch_waves (measured: 0.65 -> 0.51 ms
+    // per pass at 256 KB, but 31.0 -> 32.9 ms at 32 MB, where the margin pass wants a kernel of its own for occupancy)
+    s->dense_in_place = mode == HOP_GRAD_SVM_DENSE && (int64_t)B * c->d * 4 <= kDenseInPlaceBytes;
     std::vector<HopMixJob> mix((size_t)std::max(R, 1));
     std::vector<HopGradJob> grad;
     s->grad_begin.assign(s->n_waves + 1, 0);
@@ -138,7 +142,20 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                     gj.X = dd.X;
                     gj.y = dd.y;
                     gj.partial = c->partial + (int64_t)i * partial_floats(c->d, c->opts.batch);
-                    mj.g = gj.g;
+                    if (s->dense_in_place) {
+                        // the mix only reduces; the gradient kernel applies -eta g (through the velocity, if any)
+                        // to the reduced vector in place, so no dense g is written and read back
+                        gj.out = mj.out;
+                        gj.eta = eta;
+                        if (c->vel) {
+                            gj.vel = c->vel + (int64_t)i * c->stride;
+                            gj.mu = c->opts.momentum;
+                        }
+                        s->wave_grad_bytes[w] += 4.0 * (c->vel ? 2.0 * c->d : 0.0) + 4.0 * c->d;
+                    } else {
+                        gj.out = nullptr;              // the gradient kernel writes g, the mix applies it
+                        mj.g = gj.g;
+                    }
                     s->wave_grad_bytes[w] += 4.0 * ((double)B * c->d + 2.0 * c->d) + 8.0 * B;
                 } else if (mode == HOP_GRAD_SVM_CSR) {
                     if (!dd.rowptr || !dd.col || !dd.val || !dd.y) return HOP_ERR_STATE;
@@ -564,6 +581,15 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
             if (timed && (rc = prof_begin(c, HOP_KERNEL_SYNTH, s->wave_grad_bytes[w]))) return rc;
             HOP_LAUNCH(c, hopk_synth(gj, ng, c->d, stream));
             if (timed && (rc = prof_end(c))) return rc;
+        } else if (ng > 0 && mode == HOP_GRAD_SVM_DENSE && s->dense_in_place) {
+            // Small minibatches are bound by launches, not bytes.  Compute beside Reduce (Section 3.2): partial
+            // margins and the wave's Reduce in one launch, then the gradient kernel, which applies -eta g to the
+            // reduced vectors in place: two dependent launches per wave, not three.  Timed as gradient work.
+            if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w] + s->wave_mix_bytes[w]))) return rc;
+            HOP_LAUNCH(c, hopk_mix_dense_margin(s->mix_dev + jb, nj, c->d, gj, ng, B, stream));
+            HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, c->opts.loss, stream));
+            if (timed && (rc = prof_end(c))) return rc;
+            continue;
         } else if (ng > 0 && mode == HOP_GRAD_SVM_DENSE) {
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
             HOP_LAUNCH(c, hopk_dense_margin(gj, ng, B, c->d, stream));

@@ -33,8 +33,11 @@ struct alignas(16) HopGradJob {
     float* g;                  // dense gradient buffer of the worker (dense / synth modes)
     float* coef;               // B hinge coefficients of this record
     float* partial;            // dense: B x nseg partial dot products
-    float* out;                // csr: the vector the sparse part is scattered into
-    float* vel;                // csr with momentum: the velocity the sparse part is scattered into as well
+    float* out;                // csr: the vector the sparse part is scattered into; dense: if set, the gradient is
+                               // applied to it in place (out -= eta g) instead of being written to g
+    float* vel;                // with momentum: csr, the velocity the sparse part is scattered into as well;
+                               // dense with out set, v <- mu v + g in place and out -= eta v
+    float eta, mu;             // dense with out set
     uint32_t k0, k1, k2;       // synth: hash keys of (seed, worker, iteration)
     float scale;               // synth: fp32 factor
 };
@@ -45,6 +48,8 @@ int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream);
 int hopk_dense_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, void* stream);
 int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, int loss, void* stream);
 int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, void* stream);
+int hopk_mix_dense_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
+                          void* stream);
 int hopk_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
                         int loss, void* stream);
 int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, int into_velocity, void* stream);
@@ -80,6 +85,7 @@ struct hop_schedule {
     HopGradJob* grad_dev = nullptr;     // STEP records only, in wave order
     int32_t* rows_dev = nullptr;        // n_records x batch
     float* coef_dev = nullptr;          // n_records x batch
+    bool dense_in_place = false;        // dense SVM: margins beside the Reduce, gradient applied in place
     std::vector<int32_t> grad_begin;    // n_waves + 1 offsets into grad_dev
     std::vector<double> wave_mix_bytes; // algorithmic bytes of each wave's mix launch
     std::vector<double> wave_grad_bytes;

@@ -384,10 +384,8 @@ constexpr int kSegVec = 16;
 constexpr int kSeg4 = kThreads * kSegVec;             // float4 per segment
 constexpr int64_t kSegCols = (int64_t)kSeg4 * 4;
 
-__global__ __launch_bounds__(kThreads) void dense_margin_kernel(const HopGradJob* __restrict__ jobs, int B,
-                                                                int64_t d, int nseg) {
-    __shared__ float red[kThreads / 64];
-    const int64_t b = blockIdx.x;
+__device__ __forceinline__ void dense_margin_block(const HopGradJob* __restrict__ jobs, int B, int64_t d, int nseg,
+                                                   int64_t b, float* red) {
     const int seg = (int)(b % nseg);
     const int m = (int)((b / nseg) % B);
     const HopGradJob* job = jobs + b / ((int64_t)nseg * B);
@@ -414,6 +412,28 @@ __global__ __launch_bounds__(kThreads) void dense_margin_kernel(const HopGradJob
     }
     float tot = block_sum(acc, red);
     if (threadIdx.x == 0) job->partial[(int64_t)m * nseg + seg] = tot;
+}
+
+__global__ __launch_bounds__(kThreads) void dense_margin_kernel(const HopGradJob* __restrict__ jobs, int B,
+                                                                int64_t d, int nseg) {
+    __shared__ float red[kThreads / 64];
+    dense_margin_block(jobs, B, d, nseg, blockIdx.x, red);
+}
+
+// The partial margins of a wave's STEP records and the wave's Reduce in one launch: both only read x_k
+// (the parallel approach of Section 3.2 runs Compute beside Reduce).  The Reduce leaves sum_a w'_a x_a
+// in the result slot; dense_grad_kernel then applies -eta g to it.
+template <int VEC, int NT, int MAP>
+__global__ __launch_bounds__(kThreads) void mix_dense_margin_kernel(const HopMixJob* __restrict__ mix_jobs, int n_mix,
+                                                                    int64_t d, int64_t n_chunks,
+                                                                    const HopGradJob* __restrict__ grad_jobs, int B,
+                                                                    int nseg, int64_t margin_blocks) {
+    __shared__ float red[kThreads / 64];
+    if ((int64_t)blockIdx.x >= margin_blocks) {
+        mix_block<VEC, NT, MAP, kThreads>(mix_jobs, n_mix, d, n_chunks, (int64_t)blockIdx.x - margin_blocks);
+        return;
+    }
+    dense_margin_block(grad_jobs, B, d, nseg, blockIdx.x, red);
 }
 
 // ----------------------------------------------------- dense SVM: g = lambda w - sum_m c_m x_m ----
@@ -468,6 +488,9 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
     const float* X = job->X;
     const float* w = job->w;
     float* g = job->g;
+    float* out = job->out;                             // set: apply -eta g (or -eta v) to it instead of writing g
+    float* vel = job->vel;
+    const float neg_eta = -job->eta, mu = job->mu;
     if ((d & 3) == 0) {
         const int64_t n4 = d >> 2;
         const int64_t i = chunk * kThreads + threadIdx.x;
@@ -487,8 +510,20 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
                 }
             }
             float4 wv = ld4(w, i);
-            st4(g, i, make_float4(fmaf(lambda, wv.x, -acc.x), fmaf(lambda, wv.y, -acc.y),
-                                  fmaf(lambda, wv.z, -acc.z), fmaf(lambda, wv.w, -acc.w)));
+            float4 gv = make_float4(fmaf(lambda, wv.x, -acc.x), fmaf(lambda, wv.y, -acc.y),
+                                    fmaf(lambda, wv.z, -acc.z), fmaf(lambda, wv.w, -acc.w));
+            if (out == nullptr) {
+                st4(g, i, gv);
+            } else {                                   // Apply in place on the reduced vector
+                if (vel != nullptr) {
+                    const float4 v = ld4(vel, i);
+                    gv = make_float4(fmaf(mu, v.x, gv.x), fmaf(mu, v.y, gv.y), fmaf(mu, v.z, gv.z), fmaf(mu, v.w, gv.w));
+                    st4(vel, i, gv);
+                }
+                const float4 o = ld4(out, i);
+                st4(out, i, make_float4(fmaf(neg_eta, gv.x, o.x), fmaf(neg_eta, gv.y, o.y), fmaf(neg_eta, gv.z, o.z),
+                                        fmaf(neg_eta, gv.w, o.w)));
+            }
         }
     } else {
         for (int q = 0; q < 4; ++q) {
@@ -496,7 +531,16 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
             if (c < d) {
                 float acc = 0.f;
                 for (int n = 0; n < nact; ++n) acc = fmaf(coefS[n], X[(int64_t)rowS[n] * d + c], acc);
-                g[c] = fmaf(lambda, w[c], -acc);
+                float gv = fmaf(lambda, w[c], -acc);
+                if (out == nullptr) {
+                    g[c] = gv;
+                } else {
+                    if (vel != nullptr) {
+                        gv = fmaf(mu, vel[c], gv);
+                        vel[c] = gv;
+                    }
+                    out[c] = fmaf(neg_eta, gv, out[c]);
+                }
             }
         }
     }
@@ -688,6 +732,28 @@ int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, voi
     hipLaunchKernelGGL(csr_margin_kernel, dim3((unsigned)(n_jobs * per)), dim3(kThreads), 0, (hipStream_t)stream,
                        jobs_dev, B, per, loss);
     return launch_status();
+}
+
+template <int VEC, int NT, int MAP>
+int launch_mix_dense_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
+                            void* stream) {
+    int64_t n_chunks;
+    const int64_t grid = mix_grid<VEC, MAP, kThreads>(n_mix, d, &n_chunks);
+    const int nseg = hopk_dense_nseg(d);
+    const int64_t margin_blocks = (int64_t)n_grad * B * nseg;
+    if (grid + margin_blocks > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((mix_dense_margin_kernel<VEC, NT, MAP>), dim3((unsigned)(grid + margin_blocks)), dim3(kThreads), 0,
+                       (hipStream_t)stream, mix_dev, n_mix, d, n_chunks, grad_dev, B, nseg, margin_blocks);
+    return (int)hipGetLastError();
+}
+
+int hopk_mix_dense_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
+                          void* stream) {
+    if (n_grad <= 0 || B <= 0) return hopk_mix(mix_dev, n_mix, d, stream);
+    if (n_mix <= 0) return hopk_dense_margin(grad_dev, n_grad, B, d, stream);
+    if ((d >> 2) >= (int64_t)1024 * kThreads * 4)
+        return launch_mix_dense_margin<4, 1, 14>(mix_dev, n_mix, d, grad_dev, n_grad, B, stream);
+    return launch_mix_dense_margin<4, 1, 1>(mix_dev, n_mix, d, grad_dev, n_grad, B, stream);
 }
 
 int hopk_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,

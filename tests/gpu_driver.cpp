@@ -167,7 +167,14 @@ int main() {
                 EXPECT(hop_step(c, sched, 0, -1) == HOP_OK);
                 double ms = 0, bytes = 0;
                 int64_t launches = 0;
-                EXPECT(hop_profile_read(c, HOP_KERNEL_MIX, &ms, &launches, &bytes) == HOP_OK && launches == v.n_waves);
+                EXPECT(hop_profile_read(c, HOP_KERNEL_MIX, &ms, &launches, &bytes) == HOP_OK);
+                if (mode != HOP_GRAD_SVM_DENSE) {          // dense: the Reduce rides in the gradient launches
+                    EXPECT(launches == v.n_waves);
+                } else {
+                    int64_t grad_launches = 0;
+                    EXPECT(hop_profile_read(c, HOP_KERNEL_GRAD, &ms, &grad_launches, &bytes) == HOP_OK);
+                    EXPECT(launches + grad_launches == v.n_waves);
+                }
                 EXPECT(hop_profile(c, 0) == HOP_OK);
                 EXPECT(hop_use_graph(c, 1) == HOP_OK);
                 for (int rep = 0; rep < 3; ++rep) {
