@@ -109,7 +109,6 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
     s->wave_mix_bytes.assign(s->n_waves, 0.0);
     s->wave_grad_bytes.assign(s->n_waves, 0.0);
     const float eta = c->opts.lr;
-    const int nseg = hopk_dense_nseg(c->d);
     for (int w = 0; w < s->n_waves; ++w) {
         for (int p = s->wave_begin[w]; p < s->wave_begin[w + 1]; ++p) {
             const int e = s->wave_order[p];
@@ -130,7 +129,6 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                 std::memset(&gj, 0, sizeof(gj));
                 gj.w = mj.src[0];
                 gj.g = c->gbuf + (int64_t)i * c->stride;
-                gj.out = mj.out;
                 if (B > 0) {
                     gj.rows = s->rows_dev + (size_t)e * B;
                     gj.coef = s->coef_dev + (size_t)e * B;
@@ -153,8 +151,7 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                         }
                         s->wave_grad_bytes[w] += 4.0 * (c->vel ? 2.0 * c->d : 0.0) + 4.0 * c->d;
                     } else {
-                        gj.out = nullptr;              // the gradient kernel writes g, the mix applies it
-                        mj.g = gj.g;
+                        mj.g = gj.g;                   // the gradient kernel writes g, the mix applies it
                     }
                     s->wave_grad_bytes[w] += 4.0 * ((double)B * c->d + 2.0 * c->d) + 8.0 * B;
                 } else if (mode == HOP_GRAD_SVM_CSR) {
@@ -163,6 +160,7 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                     gj.col = dd.col;
                     gj.val = dd.val;
                     gj.y = dd.y;
+                    gj.out = mj.out;                   // where the sparse part of -eta g is scattered
                     if (c->vel) {
                         // with a velocity, lambda w goes into it inside the mix (v <- mu v + lambda x_self) and the
                         // sparse part is scattered into both the velocity (-c x) and the result (+eta c x)
@@ -193,7 +191,6 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
         }
         s->grad_begin[w + 1] = (int32_t)grad.size();
     }
-    (void)nseg;
     if (R > 0) {
         HOP_HIP(c, hipMalloc((void**)&s->mix_dev, (size_t)R * sizeof(HopMixJob)));
         HOP_HIP(c, hipMemcpy(s->mix_dev, mix.data(), (size_t)R * sizeof(HopMixJob), hipMemcpyHostToDevice));
