@@ -65,7 +65,7 @@ def cpu_baseline(c, recs, p0, budget_s=20.0):
         g = grad(r.worker, r.k, vecs[0]) if grad is not None else None
         slots[(r.worker, r.out_slot)] = arith.reduce_apply(vecs, r.w32, g, c["lr"])
         done += 1
-        if time.perf_counter() - t0 > budget_s or done >= 16:
+        if time.perf_counter() - t0 > budget_s or done >= 28:
             break
     dt = time.perf_counter() - t0
     return {"value": done / dt, "unit": "worker-updates/s", "cores": 1, "kind": "oracle",
