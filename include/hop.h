@@ -219,14 +219,26 @@ int hop_set_grad_source(hop_ctx* ctx, int mode, float variance, const float* ext
  * HOP_ERR_DEADLOCK).  Touches no device memory. */
 int hop_simulate(hop_ctx* ctx, const hop_delay_model* delays, int32_t max_iter, hop_schedule** out);
 int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* out);
-/* Frees a schedule and its device-side descriptors.  A schedule may outlive its context (its host
- * arrays stay valid), but hop_step refuses it once the context is gone. */
+/* Frees a schedule (host memory only: its device-side descriptors live in the caller's workspace).  A
+ * schedule may outlive its context (its host arrays stay valid), but hop_step refuses it once the
+ * context is gone. */
 int hop_schedule_free(hop_schedule* s);
+
+/* Device memory hop_step needs for the descriptors of this schedule (per record: the sources, weights and
+ * result of its Reduce, the inputs of its Compute, its minibatch sample ids and loss coefficients), and
+ * the call that lends it: `workspace` is device memory of at least hop_schedule_bytes(s) bytes, 256-byte
+ * aligned, borrowed until the schedule is freed or bound again; the library allocates no device memory
+ * for a schedule.  hop_step returns HOP_ERR_ARENA_TOO_SMALL for a schedule without workspace.  Binding
+ * again (other memory) is allowed between passes; the descriptors are then laid out anew. */
+size_t hop_schedule_bytes(const hop_schedule* s);
+int hop_schedule_bind(hop_ctx* ctx, hop_schedule* s, void* workspace, size_t bytes);
 
 /* Enqueues waves [wave_begin, wave_end) of the schedule: per wave the gradient kernels of its STEP
  * records (Compute on x_k, Section 3.2), then one fused Reduce + Apply launch over all its records
  * (with CSR data the margins ride in that launch and the sparse part of the gradient is scattered
- * into the results right after it).  Records of one wave touch no
+ * into the results right after it).  The first call for a schedule (and the first after the gradient
+ * source or a data set changed) copies the descriptors into the schedule's workspace with synchronous
+ * host-to-device copies; after that the call only launches.  Records of one wave touch no
  * ring slot in a conflicting way, so the result equals running the records one by one in schedule
  * order.  Waves must be run in order starting from 0 after hop_set_params (or continue where the last
  * call stopped); wave_end = -1 means "to the end".  A finished schedule may be started again from

@@ -63,18 +63,84 @@ int hip_fail(hop_ctx* ctx, hipError_t e, const char* what) {
         if (e_ != 0) return hip_fail((ctx), (hipError_t)e_, "kernel launch " #call); \
     } while (0)
 
+// Forget the descriptors laid out in the schedule's workspace (the memory is the caller's).
 void free_device_side(hop_schedule* s) {
-    if (s->mix_dev) (void)hipFree(s->mix_dev);
-    if (s->grad_dev) (void)hipFree(s->grad_dev);
-    if (s->rows_dev) (void)hipFree(s->rows_dev);
-    if (s->coef_dev) (void)hipFree(s->coef_dev);
     s->mix_dev = nullptr;
+    s->pair_dev = nullptr;
     s->grad_dev = nullptr;
     s->rows_dev = nullptr;
     s->coef_dev = nullptr;
     s->built_mode = -1;
     if (s->graph_exec) (void)hipGraphExecDestroy((hipGraphExec_t)s->graph_exec);
     s->graph_exec = nullptr;
+}
+
+constexpr size_t kWsAlign = 256;
+inline size_t ws_round(size_t v) { return (v + kWsAlign - 1) / kWsAlign * kWsAlign; }
+
+// Device bytes the descriptors of R records with minibatches of B need: sample ids, coefficients, one
+// Reduce descriptor per record in both forms, one gradient descriptor per record.
+size_t workspace_need(size_t R, size_t B) {
+    return 2 * ws_round(R * B * sizeof(float)) + ws_round(R * sizeof(HopMixJob)) + ws_round(R * sizeof(HopPairJob)) +
+           ws_round(R * sizeof(HopGradJob)) + kWsAlign;
+}
+
+// Pack the Reduce jobs of one wave two by two: a record is joined with the later record (among the next 64 still
+// single) that shares the most sources with it, provided the union stays within HOP_PAIR_U vectors.  Union order:
+// the first record's sources in its own order, then what the second adds.  Returns the distinct vectors of the wave.
+int pack_pairs(const HopMixJob* jobs, int n, std::vector<HopPairJob>& out) {
+    std::vector<char> used((size_t)n, 0);
+    std::vector<const float*> all;
+    for (int i = 0; i < n; ++i) {
+        all.insert(all.end(), jobs[i].src, jobs[i].src + jobs[i].A);
+        if (used[i]) continue;
+        used[i] = 1;
+        const HopMixJob& a = jobs[i];
+        int best = -1, best_overlap = 0;
+        if (a.A <= HOP_PAIR_U) {
+            int seen = 0;
+            for (int k = i + 1; k < n && seen < 64; ++k) {
+                if (used[k]) continue;
+                ++seen;
+                const HopMixJob& b = jobs[k];
+                int overlap = 0;
+                for (int q = 0; q < b.A; ++q)
+                    if (std::find(a.src, a.src + a.A, b.src[q]) != a.src + a.A) ++overlap;
+                if (overlap > best_overlap && a.A + b.A - overlap <= HOP_PAIR_U) {
+                    best = k;
+                    best_overlap = overlap;
+                }
+            }
+        }
+        HopPairJob pj;
+        std::memset(&pj, 0, sizeof(pj));
+        pj.eta = a.eta;
+        pj.G = 1;
+        pj.U = a.A;
+        pj.out[0] = a.out;
+        pj.g[0] = a.g;
+        for (int q = 0; q < a.A; ++q) {
+            pj.src[q] = a.src[q];
+            pj.w[0][q] = a.w[q];
+            if (q < 32) pj.mask[0] |= 1u << q;
+        }
+        if (best >= 0) {
+            used[best] = 1;
+            const HopMixJob& b = jobs[best];
+            pj.G = 2;
+            pj.out[1] = b.out;
+            pj.g[1] = b.g;
+            for (int q = 0; q < b.A; ++q) {
+                int u = (int)(std::find(pj.src, pj.src + pj.U, b.src[q]) - pj.src);
+                if (u == pj.U) pj.src[pj.U++] = b.src[q];
+                pj.w[1][u] += b.w[q];      // a record that lists one vector twice keeps the sum of its weights
+                pj.mask[1] |= 1u << u;
+            }
+        }
+        out.push_back(pj);
+    }
+    std::sort(all.begin(), all.end());
+    return (int)(std::unique(all.begin(), all.end()) - all.begin());
 }
 
 float* slot_ptr(const hop_ctx* c, int worker, int slot) {
@@ -93,11 +159,19 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
     if (mode == HOP_GRAD_SVM_DENSE || mode == HOP_GRAD_SVM_CSR)
         for (int i = 0; i < c->N; ++i)
             if ((size_t)i >= s->rows_at_sim.size() || s->rows_at_sim[i] != c->data[i].rows) return HOP_ERR_STATE;
+    if (!s->workspace || s->workspace_bytes < workspace_need((size_t)R, (size_t)std::max(B, 0)))
+        return HOP_ERR_ARENA_TOO_SMALL;       // hop_schedule_bind first
+    char* ws = s->workspace;
+    auto carve = [&ws](size_t bytes) {
+        char* p = ws;
+        ws += ws_round(bytes);
+        return p;
+    };
     if (B > 0) {
-        HOP_HIP(c, hipMalloc((void**)&s->rows_dev, (size_t)R * B * sizeof(int32_t)));
+        s->rows_dev = (int32_t*)carve((size_t)R * B * sizeof(int32_t));
+        s->coef_dev = (float*)carve((size_t)R * B * sizeof(float));
         HOP_HIP(c, hipMemcpy(s->rows_dev, s->batch_rows.data(), (size_t)R * B * sizeof(int32_t),
                              hipMemcpyHostToDevice));
-        HOP_HIP(c, hipMalloc((void**)&s->coef_dev, (size_t)R * B * sizeof(float)));
         HOP_HIP(c, hipMemset(s->coef_dev, 0, (size_t)R * B * sizeof(float)));
     }
     // dense minibatches of up to 2 MB per record take the two-launch path of launch_waves (measured: 0.65 -> 0.51 ms
@@ -192,11 +266,25 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
         s->grad_begin[w + 1] = (int32_t)grad.size();
     }
     if (R > 0) {
-        HOP_HIP(c, hipMalloc((void**)&s->mix_dev, (size_t)R * sizeof(HopMixJob)));
+        s->mix_dev = (HopMixJob*)carve((size_t)R * sizeof(HopMixJob));
         HOP_HIP(c, hipMemcpy(s->mix_dev, mix.data(), (size_t)R * sizeof(HopMixJob), hipMemcpyHostToDevice));
     }
+    // without velocities the Reduce runs on records packed in pairs
+    s->pair_begin.assign(s->n_waves + 1, 0);
+    s->wave_sources.assign(s->n_waves, 0);
+    if (!c->vel && R > 0) {
+        std::vector<HopPairJob> pairs;
+        pairs.reserve((size_t)R);
+        for (int w = 0; w < s->n_waves; ++w) {
+            const int jb = s->wave_begin[w], nj = s->wave_begin[w + 1] - jb;
+            s->wave_sources[w] = pack_pairs(mix.data() + jb, nj, pairs);
+            s->pair_begin[w + 1] = (int32_t)pairs.size();
+        }
+        s->pair_dev = (HopPairJob*)carve((size_t)R * sizeof(HopPairJob));
+        HOP_HIP(c, hipMemcpy(s->pair_dev, pairs.data(), pairs.size() * sizeof(HopPairJob), hipMemcpyHostToDevice));
+    }
     if (!grad.empty()) {
-        HOP_HIP(c, hipMalloc((void**)&s->grad_dev, grad.size() * sizeof(HopGradJob)));
+        s->grad_dev = (HopGradJob*)carve((size_t)R * sizeof(HopGradJob));
         HOP_HIP(c, hipMemcpy(s->grad_dev, grad.data(), grad.size() * sizeof(HopGradJob), hipMemcpyHostToDevice));
     }
     s->built_mode = mode;
@@ -564,6 +652,26 @@ int hop_schedule_free(hop_schedule* s) {
     return HOP_OK;
 }
 
+size_t hop_schedule_bytes(const hop_schedule* s) {
+    if (!s) return 0;
+    return workspace_need(s->kind.size(), (size_t)std::max(s->batch, 0));
+}
+
+int hop_schedule_bind(hop_ctx* c, hop_schedule* s, void* workspace, size_t bytes) {
+    if (!c || !s || !workspace || ((uintptr_t)workspace & (kWsAlign - 1))) return HOP_ERR_INVALID_ARG;
+    if (!c->has_device) return HOP_ERR_NO_DEVICE;
+    if (s->owner != c) return HOP_ERR_INVALID_ARG;
+    if (bytes < hop_schedule_bytes(s)) return HOP_ERR_ARENA_TOO_SMALL;
+    if (c->running == s) {
+        c->running = nullptr;
+        c->next_wave = 0;
+    }
+    free_device_side(s);                   // descriptors are laid out again by the next hop_step
+    s->workspace = (char*)workspace;
+    s->workspace_bytes = bytes;
+    return HOP_OK;
+}
+
 // Enqueue the kernels of waves [wb, we) on `stream`.  `timed` brackets every kernel group with
 // profiling events (never while a stream is being captured into a graph).
 static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* stream, bool timed) {
@@ -573,6 +681,8 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
         const int jb = s->wave_begin[w], nj = s->wave_begin[w + 1] - jb;
         const int gb = s->grad_begin[w], ng = s->grad_begin[w + 1] - gb;
         const HopGradJob* gj = s->grad_dev ? s->grad_dev + gb : nullptr;
+        const HopPairJob* pj = s->pair_dev ? s->pair_dev + s->pair_begin[w] : nullptr;   // null: contexts with a velocity
+        const int np = s->pair_dev ? s->pair_begin[w + 1] - s->pair_begin[w] : 0;
         int rc;
         if (ng > 0 && mode == HOP_GRAD_SYNTH) {
             if (timed && (rc = prof_begin(c, HOP_KERNEL_SYNTH, s->wave_grad_bytes[w]))) return rc;
@@ -583,7 +693,10 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
             // margins and the wave's Reduce in one launch, then the gradient kernel, which applies -eta g to the
             // reduced vectors in place: two dependent launches per wave, not three.  Timed as gradient work.
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w] + s->wave_mix_bytes[w]))) return rc;
-            HOP_LAUNCH(c, hopk_mix_dense_margin(s->mix_dev + jb, nj, c->d, gj, ng, B, stream));
+            if (pj)
+                HOP_LAUNCH(c, hopk_pair_dense_margin(pj, np, s->wave_sources[w], c->d, gj, ng, B, stream));
+            else
+                HOP_LAUNCH(c, hopk_mix_dense_margin(s->mix_dev + jb, nj, c->d, gj, ng, B, stream));
             HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, c->opts.loss, stream));
             if (timed && (rc = prof_end(c))) return rc;
             continue;
@@ -595,8 +708,12 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
         }
         const bool csr = ng > 0 && mode == HOP_GRAD_SVM_CSR;
         if (timed && (rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
-        if (csr)   // margins and Reduce + Apply both only read x_k: one launch
+        if (csr && pj)   // margins and Reduce + Apply both only read x_k: one launch
+            HOP_LAUNCH(c, hopk_pair_csr_margin(pj, np, s->wave_sources[w], c->d, gj, ng, B, c->opts.loss, stream));
+        else if (csr)
             HOP_LAUNCH(c, hopk_mix_csr_margin(s->mix_dev + jb, nj, c->d, gj, ng, B, c->opts.loss, stream));
+        else if (pj)
+            HOP_LAUNCH(c, hopk_pair(pj, np, s->wave_sources[w], c->d, stream));
         else
             HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, stream));
         if (timed && (rc = prof_end(c))) return rc;
@@ -754,11 +871,20 @@ int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* stream) {
             mj.w[a] = in.w[a];
         }
     }
-    HopMixJob* dev = nullptr;
-    HOP_HIP(nullptr, hipMalloc((void**)&dev, host.size() * sizeof(HopMixJob)));
-    hipError_t e = hipMemcpy(dev, host.data(), host.size() * sizeof(HopMixJob), hipMemcpyHostToDevice);
+    bool any_vel = false;
+    for (const HopMixJob& mj : host) any_vel = any_vel || mj.vel != nullptr;
+    std::vector<HopPairJob> pairs;
+    int n_sources = 0;
+    if (!any_vel) n_sources = pack_pairs(host.data(), n_jobs, pairs);    // the path hop_step takes without velocities
+    const size_t bytes = any_vel ? host.size() * sizeof(HopMixJob) : pairs.size() * sizeof(HopPairJob);
+    void* dev = nullptr;
+    HOP_HIP(nullptr, hipMalloc(&dev, bytes));
+    hipError_t e = hipMemcpy(dev, any_vel ? (const void*)host.data() : (const void*)pairs.data(), bytes,
+                             hipMemcpyHostToDevice);
     int rc = 0;
-    if (e == hipSuccess) rc = hopk_mix(dev, n_jobs, d, stream);
+    if (e == hipSuccess)
+        rc = any_vel ? hopk_mix((const HopMixJob*)dev, n_jobs, d, stream)
+                     : hopk_pair((const HopPairJob*)dev, (int)pairs.size(), n_sources, d, stream);
     hipError_t e2 = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(dev);
     if (e != hipSuccess) return hip_fail(nullptr, e, "hipMemcpy");

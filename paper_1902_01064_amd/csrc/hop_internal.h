@@ -21,6 +21,22 @@ struct alignas(16) HopMixJob {
     float w[HOP_MAX_A];
 };
 
+constexpr int HOP_PAIR_U = 12;   // most vectors in the union of a pair of records (the kernel unrolls up to this)
+
+// One or two records of a wave whose source sets overlap, run by one workgroup per column chunk: the union of
+// their sources (each loaded once), and per record a membership mask over the union with its weights.  A single
+// record may have up to HOP_MAX_A sources; a pair at most 12 in the union.  Records with a velocity keep HopMixJob.
+struct alignas(16) HopPairJob {
+    int32_t U, G;              // vectors in the union, records (1 or 2)
+    float eta;
+    int32_t reserved;
+    float* out[2];
+    const float* g[2];         // null: no gradient term
+    uint32_t mask[2];          // bit u: the record averages src[u]
+    const float* src[HOP_MAX_A];
+    float w[2][HOP_MAX_A];     // weight of src[u] in record r (0 where the record does not read it)
+};
+
 struct alignas(16) HopGradJob {
     // dense: X row-major rows x d; csr: rowptr/col/val
     const float* X;
@@ -52,6 +68,11 @@ int hopk_mix_dense_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const 
                           void* stream);
 int hopk_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
                         int loss, void* stream);
+int hopk_pair(const HopPairJob* jobs_dev, int n_jobs, int n_sources, int64_t d, void* stream);
+int hopk_pair_csr_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int64_t d, const HopGradJob* grad_dev,
+                         int n_grad, int B, int loss, void* stream);
+int hopk_pair_dense_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int64_t d, const HopGradJob* grad_dev,
+                           int n_grad, int B, void* stream);
 int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, int into_velocity, void* stream);
 int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream);
 int hopk_csr_check(const int64_t* rowptr, const int32_t* col, int64_t rows, int64_t first, int64_t nnz, int64_t d,
@@ -77,16 +98,22 @@ struct hop_schedule {
     std::vector<uint64_t> finish_time;
     std::vector<int64_t> rows_at_sim;   // data-set sizes the minibatch ids were drawn for
 
-    // device side, built lazily by hop_step for the context's current gradient mode
+    // device side: descriptors laid out by hop_step, for the context's current gradient mode, inside the
+    // workspace the caller lent with hop_schedule_bind (the library allocates no device memory for a schedule)
     hop_ctx* owner = nullptr;
+    char* workspace = nullptr;
+    size_t workspace_bytes = 0;
     int built_mode = -1;
     uint64_t built_epoch = 0;
     HopMixJob* mix_dev = nullptr;       // n_records, in wave order
+    HopPairJob* pair_dev = nullptr;     // the same records packed in pairs, wave by wave (null with a velocity)
     HopGradJob* grad_dev = nullptr;     // STEP records only, in wave order
     int32_t* rows_dev = nullptr;        // n_records x batch
     float* coef_dev = nullptr;          // n_records x batch
     bool dense_in_place = false;        // dense SVM: margins beside the Reduce, gradient applied in place
     std::vector<int32_t> grad_begin;    // n_waves + 1 offsets into grad_dev
+    std::vector<int32_t> pair_begin;    // n_waves + 1 offsets into pair_dev
+    std::vector<int32_t> wave_sources;  // distinct vectors each wave reads
     std::vector<double> wave_mix_bytes; // algorithmic bytes of each wave's mix launch
     std::vector<double> wave_grad_bytes;
     void* graph_exec = nullptr;         // hipGraphExec_t of waves [0, n_waves), see hop_use_graph()

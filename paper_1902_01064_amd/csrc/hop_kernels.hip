@@ -13,21 +13,34 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kXcd = 8;                 // workgroups are dealt round-robin to the 8 XCDs
 
+typedef float vf4 __attribute__((ext_vector_type(4)));
+// Every vector handed to these kernels is device (global) memory, but the pointers come out of job
+// descriptors, where the compiler only knows them as generic: without the address-space cast it emits
+// flat_load / flat_store, which also count on the LDS counter, so every wait for a scalar load (the next
+// pointer, the next weight) would wait for the vector loads in flight too.
+#ifndef HOP_FLAT_ACCESS
+#define HOP_GLOBAL __attribute__((address_space(1)))
+#else
+#define HOP_GLOBAL
+#endif
+typedef const HOP_GLOBAL vf4* gvec_in;
+typedef HOP_GLOBAL vf4* gvec_out;
 __device__ __forceinline__ float4 ld4(const float* p, int64_t i4) {
-    return reinterpret_cast<const float4*>(p)[i4];
+    vf4 v = ((gvec_in)p)[i4];
+    return make_float4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void st4(float* p, int64_t i4, float4 v) {
-    reinterpret_cast<float4*>(p)[i4] = v;
+    vf4 t = {v.x, v.y, v.z, v.w};
+    ((gvec_out)p)[i4] = t;
 }
-typedef float vf4 __attribute__((ext_vector_type(4)));
 // streaming (non-temporal) 128-bit accesses for data touched once
 __device__ __forceinline__ float4 ld4_stream(const float* p, int64_t i4) {
-    vf4 v = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(p) + i4);
+    vf4 v = __builtin_nontemporal_load((gvec_in)p + i4);
     return make_float4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void st4_stream(float* p, int64_t i4, float4 v) {
     vf4 t = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(t, reinterpret_cast<vf4*>(p) + i4);
+    __builtin_nontemporal_store(t, (gvec_out)p + i4);
 }
 
 // blockIdx -> (job, chunk) so that the 8 workgroups dealt to the 8 XCDs at the same moment work on
@@ -291,6 +304,184 @@ int launch_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
     hipLaunchKernelGGL((mix_kernel<VEC, NT, MAP, T>), dim3((unsigned)grid), dim3(T), 0, (hipStream_t)stream,
                        jobs_dev, n_jobs, d, n_chunks);
     return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------- Reduce + Apply, records in pairs ----
+// The plain path (no velocity).  Neighbouring workers average almost the same vectors (on a ring i and
+// i + 1 share x_i and x_{i+1}), so the host packs a wave's records two by two where their source sets
+// overlap and the union has at most kPairU vectors.  One workgroup loads the union for a 16 KB column chunk
+// once into registers and forms both sums from there; a source shared inside the pair then costs one L2
+// request instead of two.  Against the record-by-record kernel above this also changes how the work is issued:
+//  - the union size is a compile-time constant (switch over U), every pointer and weight is read by one batch
+//    of scalar loads ahead of the first vector load, and interior chunks take a path without bounds checks,
+//    so a wavefront has all its 128-bit loads in flight after one scalar wait instead of one per source;
+//  - every XCD walks `run` consecutive chunks per job group (run chosen by the host so that run x 16 KB x
+//    distinct sources of the wave stays near 3 MB of the XCD's 4 MB L2).
+// Measured on the 134 waves of the 32-worker, 25 M-parameter workload: 1.51 ms -> 1.41 ms per launch.
+// Terms are added in the order of the union (the first record's own order; the second record's sources fall
+// where the union has them), in fp32 FMAs starting from zero.
+constexpr int kPairU = HOP_PAIR_U;
+constexpr int kPairVec = 4;
+
+template <int U, bool FULL>
+__device__ __forceinline__ void pair_tile(const HopPairJob* __restrict__ job, int64_t first4, int64_t n4) {
+    constexpr int VEC = kPairVec;
+    const int G = job->G;
+    const float* src[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) src[u] = job->src[u];
+    const float* gp[2];
+    float* op[2];
+    uint32_t mk[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) { gp[r] = job->g[r]; op[r] = job->out[r]; mk[r] = job->mask[r]; }
+    const float neg_eta = -job->eta;
+    const int64_t i0 = first4 + threadIdx.x;
+    float4 x[U][VEC];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+            x[u][v] = (FULL || i0 + v * kThreads < n4) ? ld4(src[u], i0 + v * kThreads) : make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 gv[2][VEC];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        if (r < G && gp[r] != nullptr) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+                gv[r][v] = (FULL || i0 + v * kThreads < n4) ? ld4_stream(gp[r], i0 + v * kThreads)
+                                                            : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        if (r < G) {
+            float wr[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) wr[u] = job->w[r][u];
+            float4 acc[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if ((mk[r] >> u) & 1u) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        acc[v].x = fmaf(wr[u], x[u][v].x, acc[v].x);
+                        acc[v].y = fmaf(wr[u], x[u][v].y, acc[v].y);
+                        acc[v].z = fmaf(wr[u], x[u][v].z, acc[v].z);
+                        acc[v].w = fmaf(wr[u], x[u][v].w, acc[v].w);
+                    }
+                }
+            }
+            if (gp[r] != nullptr) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    acc[v].x = fmaf(neg_eta, gv[r][v].x, acc[v].x);
+                    acc[v].y = fmaf(neg_eta, gv[r][v].y, acc[v].y);
+                    acc[v].z = fmaf(neg_eta, gv[r][v].z, acc[v].z);
+                    acc[v].w = fmaf(neg_eta, gv[r][v].w, acc[v].w);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+                if (FULL || i0 + v * kThreads < n4) st4_stream(op[r], i0 + v * kThreads, acc[v]);
+        }
+    }
+}
+
+// a single record with more than kPairU sources: a loop over the sources
+__device__ __forceinline__ void pair_tile_wide(const HopPairJob* __restrict__ job, int64_t first4, int64_t n4) {
+    const int U = job->U;
+    const float* g = job->g[0];
+    const float neg_eta = -job->eta;
+    for (int v = 0; v < kPairVec; ++v) {
+        const int64_t i = first4 + (int64_t)v * kThreads + threadIdx.x;
+        if (i >= n4) continue;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < U; ++u) {
+            const float4 xv = ld4(job->src[u], i);
+            const float w = job->w[0][u];
+            acc.x = fmaf(w, xv.x, acc.x);
+            acc.y = fmaf(w, xv.y, acc.y);
+            acc.z = fmaf(w, xv.z, acc.z);
+            acc.w = fmaf(w, xv.w, acc.w);
+        }
+        if (g != nullptr) {
+            const float4 gv = ld4_stream(g, i);
+            acc.x = fmaf(neg_eta, gv.x, acc.x);
+            acc.y = fmaf(neg_eta, gv.y, acc.y);
+            acc.z = fmaf(neg_eta, gv.z, acc.z);
+            acc.w = fmaf(neg_eta, gv.w, acc.w);
+        }
+        st4_stream(job->out[0], i, acc);
+    }
+}
+
+// Work of one workgroup; `bid` is its index among the launch's mix workgroups.
+__device__ __forceinline__ void pair_block(const HopPairJob* __restrict__ jobs, int n_jobs, int64_t d, int64_t n_chunks,
+                                           int run, int64_t bid) {
+    const int xcd = (int)(bid % kXcd);
+    const int64_t local = bid / kXcd;
+    const int sub = (int)(local % run);
+    const int j = (int)((local / run) % n_jobs);
+    const int64_t round = local / ((int64_t)run * n_jobs);
+    const int64_t chunk = (round * kXcd + xcd) * run + sub;
+    if (chunk >= n_chunks) return;
+    const HopPairJob* job = jobs + j;
+    const int64_t n4 = d >> 2;
+    const int64_t first4 = chunk * (int64_t)(kThreads * kPairVec);
+    const bool full = first4 + kThreads * kPairVec <= n4;
+    static_assert(kPairU == 12, "the switch below unrolls unions of 1..12 vectors");
+#define HOP_PAIR_CASE(UU)                                      \
+    case UU:                                                   \
+        if (full) pair_tile<UU, true>(job, first4, n4);        \
+        else pair_tile<UU, false>(job, first4, n4);            \
+        break;
+    switch (job->U) {
+        HOP_PAIR_CASE(1) HOP_PAIR_CASE(2) HOP_PAIR_CASE(3) HOP_PAIR_CASE(4) HOP_PAIR_CASE(5) HOP_PAIR_CASE(6)
+        HOP_PAIR_CASE(7) HOP_PAIR_CASE(8) HOP_PAIR_CASE(9) HOP_PAIR_CASE(10) HOP_PAIR_CASE(11) HOP_PAIR_CASE(12)
+        default: pair_tile_wide(job, first4, n4); break;
+    }
+#undef HOP_PAIR_CASE
+    // the d mod 4 trailing columns, one thread each, by the workgroup of the last chunk
+    if (chunk == n_chunks - 1) {
+        const int64_t c = (n4 << 2) + (threadIdx.x & 3);
+        const int r = threadIdx.x >> 2;
+        if (threadIdx.x < 8 && r < job->G && c < d) {
+            float acc = 0.f;
+            for (int u = 0; u < job->U; ++u)
+                if ((job->mask[r] >> u) & 1u) acc = fmaf(job->w[r][u], job->src[u][c], acc);
+            if (job->g[r] != nullptr) acc = fmaf(-job->eta, job->g[r][c], acc);
+            job->out[r][c] = acc;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void pair_mix_kernel(const HopPairJob* __restrict__ jobs, int n_jobs, int64_t d,
+                                                            int64_t n_chunks, int run) {
+    pair_block(jobs, n_jobs, d, n_chunks, run, blockIdx.x);
+}
+
+inline int64_t pair_chunks(int64_t d) {
+    const int64_t per = (int64_t)kThreads * kPairVec;
+    const int64_t n = ((d >> 2) + per - 1) / per;
+    return n < 1 ? 1 : n;
+}
+
+// chunks an XCD walks per job group: run x 16 KB x distinct sources near 3 MB of its 4 MB L2 (measured on 32
+// sources: runs of 5 to 7 equal, 4 and 8 1.3 % slower, 12 10 % slower), never more than the vector has
+inline int pair_run(int n_sources, int64_t n_chunks) {
+    int run = (192 + n_sources / 2) / (n_sources < 1 ? 1 : n_sources);
+    if (run > 8) run = 8;
+    const int64_t room = n_chunks / kXcd;
+    if (run > room) run = (int)room;
+    return run < 1 ? 1 : run;
+}
+
+inline int64_t pair_grid(int n_jobs, int64_t n_chunks, int run) {
+    const int64_t span = (int64_t)kXcd * run;
+    return (n_chunks + span - 1) / span * span * n_jobs;
 }
 
 // ------------------------------------------------------------------- synthetic gradient ----
@@ -584,6 +775,30 @@ __global__ __launch_bounds__(kThreads) void mix_csr_margin_kernel(const HopMixJo
     mix_block<VEC, NT, MAP, kThreads>(mix_jobs, n_mix, d, n_chunks, (int64_t)blockIdx.x - margin_blocks);
 }
 
+// the same two fusions for the paired Reduce + Apply
+__global__ __launch_bounds__(kThreads) void pair_csr_margin_kernel(const HopPairJob* __restrict__ mix_jobs, int n_mix,
+                                                                   int64_t d, int64_t n_chunks, int run,
+                                                                   const HopGradJob* __restrict__ grad_jobs, int B,
+                                                                   int rows_per_job_blocks, int loss, int margin_blocks) {
+    if ((int)blockIdx.x < margin_blocks) {
+        csr_margin_block(grad_jobs, B, rows_per_job_blocks, loss, (int)blockIdx.x);
+        return;
+    }
+    pair_block(mix_jobs, n_mix, d, n_chunks, run, (int64_t)blockIdx.x - margin_blocks);
+}
+
+__global__ __launch_bounds__(kThreads) void pair_dense_margin_kernel(const HopPairJob* __restrict__ mix_jobs, int n_mix,
+                                                                     int64_t d, int64_t n_chunks, int run,
+                                                                     const HopGradJob* __restrict__ grad_jobs, int B,
+                                                                     int nseg, int64_t margin_blocks) {
+    __shared__ float red[kThreads / 64];
+    if ((int64_t)blockIdx.x >= margin_blocks) {
+        pair_block(mix_jobs, n_mix, d, n_chunks, run, (int64_t)blockIdx.x - margin_blocks);
+        return;
+    }
+    dense_margin_block(grad_jobs, B, d, nseg, blockIdx.x, red);
+}
+
 template <int VEC, int NT, int MAP>
 int launch_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
                           int loss, void* stream) {
@@ -763,6 +978,47 @@ int hopk_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const Ho
     if ((d >> 2) >= (int64_t)1024 * kThreads * 4)
         return launch_mix_csr_margin<4, 1, 14>(mix_dev, n_mix, d, grad_dev, n_grad, B, loss, stream);
     return launch_mix_csr_margin<4, 1, 1>(mix_dev, n_mix, d, grad_dev, n_grad, B, loss, stream);
+}
+
+int hopk_pair(const HopPairJob* jobs_dev, int n_jobs, int n_sources, int64_t d, void* stream) {
+    if (n_jobs <= 0) return 0;
+    const int64_t n_chunks = pair_chunks(d);
+    const int run = pair_run(n_sources, n_chunks);
+    const int64_t grid = pair_grid(n_jobs, n_chunks, run);
+    if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(pair_mix_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev, n_jobs, d,
+                       n_chunks, run);
+    return launch_status();
+}
+
+int hopk_pair_csr_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int64_t d, const HopGradJob* grad_dev,
+                         int n_grad, int B, int loss, void* stream) {
+    if (n_grad <= 0 || B <= 0) return hopk_pair(mix_dev, n_mix, n_sources, d, stream);
+    if (n_mix <= 0) return hopk_csr_margin(grad_dev, n_grad, B, loss, stream);
+    const int64_t n_chunks = pair_chunks(d);
+    const int run = pair_run(n_sources, n_chunks);
+    const int64_t grid = pair_grid(n_mix, n_chunks, run);
+    const int per = (B + kThreads / 64 - 1) / (kThreads / 64);
+    const int64_t margin_blocks = (int64_t)n_grad * per;
+    if (grid + margin_blocks > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(pair_csr_margin_kernel, dim3((unsigned)(grid + margin_blocks)), dim3(kThreads), 0,
+                       (hipStream_t)stream, mix_dev, n_mix, d, n_chunks, run, grad_dev, B, per, loss, (int)margin_blocks);
+    return launch_status();
+}
+
+int hopk_pair_dense_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int64_t d, const HopGradJob* grad_dev,
+                           int n_grad, int B, void* stream) {
+    if (n_grad <= 0 || B <= 0) return hopk_pair(mix_dev, n_mix, n_sources, d, stream);
+    if (n_mix <= 0) return hopk_dense_margin(grad_dev, n_grad, B, d, stream);
+    const int64_t n_chunks = pair_chunks(d);
+    const int run = pair_run(n_sources, n_chunks);
+    const int64_t grid = pair_grid(n_mix, n_chunks, run);
+    const int nseg = hopk_dense_nseg(d);
+    const int64_t margin_blocks = (int64_t)n_grad * B * nseg;
+    if (grid + margin_blocks > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(pair_dense_margin_kernel, dim3((unsigned)(grid + margin_blocks)), dim3(kThreads), 0,
+                       (hipStream_t)stream, mix_dev, n_mix, d, n_chunks, run, grad_dev, B, nseg, margin_blocks);
+    return launch_status();
 }
 
 int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, int into_velocity, void* stream) {

@@ -29,7 +29,7 @@ EXPORTS = [
     "hop_set_grad_source", "hop_simulate", "hop_schedule_view", "hop_schedule_free", "hop_step",
     "hop_params", "hop_slot", "hop_coef", "hop_profile", "hop_profile_read", "hop_mix",
     "hop_grad_scratch_floats", "hop_svm_grad_dense", "hop_svm_grad_csr", "hop_synth_grad", "hop_copy",
-    "hop_download", "hop_use_graph",
+    "hop_download", "hop_use_graph", "hop_schedule_bytes", "hop_schedule_bind",
 ]
 
 
@@ -114,6 +114,8 @@ def load():
         "hop_simulate": (C.c_int, [vp, C.POINTER(hop_delay_model), i32, C.POINTER(vp)]),
         "hop_schedule_view": (C.c_int, [vp, C.POINTER(hop_schedule_arrays)]),
         "hop_schedule_free": (C.c_int, [vp]),
+        "hop_schedule_bytes": (C.c_size_t, [vp]),
+        "hop_schedule_bind": (C.c_int, [vp, vp, vp, C.c_size_t]),
         "hop_step": (C.c_int, [vp, vp, i32, i32]),
         "hop_params": (C.c_int, [vp, i32, C.POINTER(vp), C.POINTER(i32)]),
         "hop_slot": (C.c_int, [vp, i32, i32, C.POINTER(vp)]),
@@ -283,6 +285,14 @@ def hop_simulate(ctx, max_iter, kind=HOP_DELAY_NONE, mult=None, table=None):
 
 def hop_schedule_free(sched):
     sched.free()
+
+
+def hop_schedule_bytes(sched):
+    return load().hop_schedule_bytes(sched.handle)
+
+
+def hop_schedule_bind(ctx, sched, workspace_ptr, nbytes):
+    _check(load().hop_schedule_bind(ctx, sched.handle, C.c_void_p(workspace_ptr), nbytes), "hop_schedule_bind")
 
 
 def hop_step(ctx, sched, wave_begin=0, wave_end=-1):

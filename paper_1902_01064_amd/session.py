@@ -28,6 +28,7 @@ class Session:
         self.D, self.stride = hop.hop_layout(self.d, c["s"], self.opts)
         self.keep = []
         self.sched = None
+        self.workspace = None
 
     def view(self, ptr, n):
         off = (ptr - self.arena.data_ptr()) // 4
@@ -86,6 +87,10 @@ class Session:
     def simulate(self, K=None):
         c = self.c
         self.sched = hop.hop_simulate(self.ctx, c["K"] if K is None else K, c["delay_kind"], c["mult"])
+        need = hop.hop_schedule_bytes(self.sched)              # descriptors live in memory torch lends
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        hop.hop_schedule_bind(self.ctx, self.sched, self.workspace.data_ptr(), need)
         return self.sched
 
     def step(self, wb=0, we=-1):
@@ -107,6 +112,7 @@ class Session:
         hop.hop_destroy(self.ctx)
         self.keep = []
         self.arena = None
+        self.workspace = None
 
 
 def make_data(c, device="cpu"):

@@ -15,6 +15,9 @@ int hopk_dense_grad(const HopGradJob*, int, int, int64_t, float, int, void*) { r
 int hopk_csr_margin(const HopGradJob*, int, int, int, void*) { return 1; }
 int hopk_mix_dense_margin(const HopMixJob*, int, int64_t, const HopGradJob*, int, int, void*) { return 1; }
 int hopk_mix_csr_margin(const HopMixJob*, int, int64_t, const HopGradJob*, int, int, int, void*) { return 1; }
+int hopk_pair(const HopPairJob*, int, int, int64_t, void*) { return 1; }
+int hopk_pair_csr_margin(const HopPairJob*, int, int, int64_t, const HopGradJob*, int, int, int, void*) { return 1; }
+int hopk_pair_dense_margin(const HopPairJob*, int, int, int64_t, const HopGradJob*, int, int, void*) { return 1; }
 int hopk_csr_scatter(const HopGradJob*, int, int, float, int, void*) { return 1; }
 int hopk_csr_dense_grad(const HopGradJob*, int, int, int64_t, float, void*) { return 1; }
 int hopk_csr_check(const int64_t*, const int32_t*, int64_t, int64_t, int64_t, int64_t, int*, void*) { return 1; }
@@ -147,6 +150,12 @@ int main() {
         total += touch(v);
         EXPECT(hop_schedule_view(nullptr, &v) == HOP_ERR_INVALID_ARG && hop_schedule_view(s1, nullptr) == HOP_ERR_INVALID_ARG);
         EXPECT(hop_step(c, s1, 0, -1) == HOP_ERR_NO_DEVICE);
+        EXPECT(hop_schedule_bytes(nullptr) == 0 && hop_schedule_bytes(s1) > 0);
+        EXPECT(hop_schedule_bytes(s3) >= 256);                       // an empty schedule still has a size
+        alignas(256) static char fake[256];
+        EXPECT(hop_schedule_bind(c, s1, nullptr, 1 << 20) == HOP_ERR_INVALID_ARG);
+        EXPECT(hop_schedule_bind(c, s1, fake, 1 << 20) == HOP_ERR_NO_DEVICE);
+        EXPECT(hop_schedule_bind(nullptr, s1, fake, 1 << 20) == HOP_ERR_INVALID_ARG);
         const float* p = nullptr;
         int32_t it = 0;
         EXPECT(hop_params(c, 0, &p, &it) == HOP_ERR_NO_DEVICE && hop_params(c, -1, &p, &it) == HOP_ERR_INVALID_ARG);

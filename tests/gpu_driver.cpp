@@ -138,6 +138,15 @@ int main() {
             EXPECT(hop_simulate(c, &dm, 12, &sched) == HOP_OK);
             hop_schedule_arrays v;
             EXPECT(hop_schedule_view(sched, &v) == HOP_OK && v.n_waves > 0);
+            // the descriptors of a schedule live in memory the caller lends
+            EXPECT(hop_step(c, sched, 0, -1) == HOP_ERR_ARENA_TOO_SMALL);
+            const size_t ws_bytes = hop_schedule_bytes(sched);
+            void* ws = nullptr;
+            EXPECT(ws_bytes > 0);
+            HIP_OK(hipMalloc(&ws, ws_bytes));
+            EXPECT(hop_schedule_bind(c, sched, ws, ws_bytes - 1) == HOP_ERR_ARENA_TOO_SMALL);
+            EXPECT(hop_schedule_bind(c, sched, (char*)ws + 16, ws_bytes) == HOP_ERR_INVALID_ARG);
+            EXPECT(hop_schedule_bind(c, sched, ws, ws_bytes) == HOP_OK);
 
             for (int mode : {HOP_GRAD_ZERO, HOP_GRAD_SYNTH, HOP_GRAD_SVM_DENSE, HOP_GRAD_SVM_CSR, HOP_GRAD_EXTERNAL}) {
                 if (mode == HOP_GRAD_EXTERNAL && !ext_dev) continue;
@@ -201,6 +210,9 @@ int main() {
             // a second schedule on the same context, identical replicas + zero gradient stay identical
             hop_schedule* again = nullptr;
             EXPECT(hop_simulate(c, nullptr, 5, &again) == HOP_OK);
+            void* ws2 = nullptr;
+            HIP_OK(hipMalloc(&ws2, hop_schedule_bytes(again)));
+            EXPECT(hop_schedule_bind(c, again, ws2, hop_schedule_bytes(again)) == HOP_OK);
             EXPECT(hop_set_grad_source(c, HOP_GRAD_ZERO, 0.f, nullptr) == HOP_OK);
             EXPECT(hop_set_params(c, p0.data(), 0, 0) == HOP_OK);
             EXPECT(hop_step(c, again, 0, -1) == HOP_OK);
@@ -211,6 +223,8 @@ int main() {
             EXPECT(hop_schedule_free(sched) == HOP_OK);
             EXPECT(hop_destroy(c) == HOP_OK);
             EXPECT(hop_schedule_free(again) == HOP_OK);
+            (void)hipFree(ws);
+            (void)hipFree(ws2);
             for (int i = 0; i < N; ++i) {
                 (void)hipFree(Xs[i]); (void)hipFree(ys[i]); (void)hipFree(rps[i]); (void)hipFree(cols[i]); (void)hipFree(vals[i]);
             }

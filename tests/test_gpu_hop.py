@@ -1,10 +1,12 @@
 """GPU parity of the whole path (hop_init / hop_simulate / hop_step / hop_params through the C
 ABI) against the CPU oracle on the five synthetic workloads.
 
-Bars: schedules and accepted-slot indices bit-exact; fp32 parameters within a maximum relative
-error of 1e-5 for every single record (same inputs on both sides) and 1e-4 after the whole run
-(at most 100 iterations here).  The relative error is max_c |gpu - ref| / max(|ref_c|, rms(ref))
-(tests/parity.py says why); the figure with a floor of 1e-3 rms is printed beside it.  At a hinge margin within fp32 rounding of 1 either branch is a valid
+Bars: schedules and accepted-slot indices bit-exact.  fp32 parameters: every single record, run on
+the oracle's own inputs, within the element-wise rounding bound of its fp32 sum (tests/parity.py,
+forward_excess <= 1); on the five named workloads also within a maximum relative error of 1e-5 per
+record and 1e-4 after the whole run (at most 100 iterations here), the relative error being
+max_c |gpu - ref| / max(|ref_c|, 1e-3 rms(ref)); runs of random modes and degenerate shapes are held to
+1e-4 with the floor at rms(ref).  At a hinge margin within fp32 rounding of 1 either branch is a valid
 subgradient: the oracle then follows the branch the kernel took, and the test checks that the
 margin really was that close.
 """
@@ -14,7 +16,7 @@ import torch
 
 from oracle import arith, protocol, rng, waves
 from paper_1902_01064_amd import hop, inputs
-from parity import rel_err, strict_rel_err
+from parity import forward_excess, rel_err, strict_rel_err
 from paper_1902_01064_amd.session import Session, make_data
 
 pytestmark = pytest.mark.gpu
@@ -92,6 +94,64 @@ def oracle_grad(c, data, cols=None):
     return arith.GradZero(), None
 
 
+class KeepGradient:
+    """Passes a gradient callable through and remembers what it returned."""
+
+    def __init__(self, inner):
+        self.inner, self.last = inner, None
+
+    def __call__(self, i, k, w):
+        self.last = self.inner(i, k, w)
+        return self.last
+
+
+def record_terms(c, data_np, base, rec, vecs, g, vel_before, mu, scale_of):
+    """Sum of magnitudes and count of the fp32 terms one record adds up, per column, for the forward
+    bound: the A weighted vectors, eta times the gradient's own terms (lambda w and one c_m x_m per
+    minibatch sample that contributes: the kernels sum them in fp32 too), mu v with momentum.  Third
+    value: slack for the loss coefficients of the log loss, which inherit the fp32 margin's error."""
+    eta = float(np.float32(c["lr"]))
+    mag = sum(abs(float(w)) * np.abs(x.astype(np.float64)) for w, x in zip(rec.w32, vecs))
+    n = np.full(vecs[0].shape, float(len(vecs)))
+    extra = 0.0
+    if rec.kind != protocol.STEP or g is None:
+        return mag, n, extra
+    gm, gn = np.abs(np.asarray(g, np.float64)), 1.0
+    if c["model"] in ("dense", "csr"):
+        rows, margins, act = base.log[(rec.worker, rec.k)]
+        B, lam = len(rows), float(c["lam"])
+        w64 = vecs[0].astype(np.float64)
+        gm = lam * np.abs(w64)
+        gn = np.ones_like(gm)
+        cm = np.zeros_like(gm)                       # sum_m |c_m| dm_m |x_m|: what a margin error does to g
+        if c["model"] == "dense":
+            X, y = data_np
+            yb = y[rec.worker][rows].astype(np.float64)
+            coef, _ = arith.loss_coefficients(yb, margins, B, LOSS[c.get("loss", 0)], act)
+            Xa = np.abs(X[rec.worker][rows].astype(np.float64))
+            gm = gm + np.abs(coef) @ Xa
+            gn = gn + 2.0 * float(np.count_nonzero(coef))        # the coefficient is rounded, then the product
+            if c.get("loss", 0) == 1:
+                cm = (np.abs(coef) * 1e-5 * (1.0 + scale_of(rec.worker, rows, vecs[0]))) @ Xa
+        else:
+            rp, cn, vn, y = data_np[rec.worker]
+            yb = np.array([float(y[r]) for r in rows])
+            coef, _ = arith.loss_coefficients(yb, margins, B, LOSS[c.get("loss", 0)], act)
+            sc = scale_of(rec.worker, rows, vecs[0]) if c.get("loss", 0) == 1 else None
+            for m, r in enumerate(rows):
+                if coef[m] != 0.0:
+                    lo, hi = int(rp[r]), int(rp[r + 1])
+                    np.add.at(gm, cn[lo:hi], abs(coef[m]) * np.abs(vn[lo:hi].astype(np.float64)))
+                    np.add.at(gn, cn[lo:hi], 2.0)
+                    if sc is not None:
+                        np.add.at(cm, cn[lo:hi], abs(coef[m]) * 1e-5 * (1.0 + sc[m]) * np.abs(vn[lo:hi].astype(np.float64)))
+        extra = eta * cm
+    if vel_before is not None:
+        gm = gm + float(np.float32(mu)) * np.abs(vel_before.astype(np.float64))
+        gn = gn + 1.0
+    return mag + eta * gm, n + gn, extra
+
+
 def attach(sess, c, p0, data):
     if c["model"] == "dense":
         sess.set_dense(*data)
@@ -107,7 +167,7 @@ def read_active(sess, sched, recs):
     return {(r.worker, r.k): sess.coef(e) != 0 for e, r in enumerate(recs) if r.kind == protocol.STEP}
 
 
-def run_parity(c, per_wave_check=True):
+def run_parity(c, per_wave_check=True, strict=False, strict_run_tol=None):
     """Whole run on the GPU and in the oracle.  The oracle never takes a value from the GPU: the run
     as a whole starts both from p0, and the per-record check loads the ORACLE's state into the rings
     before every wave.  (The one GPU decision the oracle follows is which side of the hinge a margin
@@ -121,6 +181,11 @@ def run_parity(c, per_wave_check=True):
         sched = sess.simulate()
         assert_schedule_equal(sched, h, recs)
         base, scale_of = oracle_grad(c, data)
+        data_np = None
+        if c["model"] == "dense":
+            data_np = ([x.numpy() for x in data[0]], [t.numpy() for t in data[1]])
+        elif c["model"] == "csr":
+            data_np = [tuple(t.numpy() for t in dd) for dd in data]
         has_hinge = c["model"] in ("dense", "csr") and c.get("loss", 0) == 0
         mu = float(c.get("momentum", 0.0))
         N, d = c["N"], c["d"]
@@ -144,7 +209,7 @@ def run_parity(c, per_wave_check=True):
         flips = grad.flips if has_hinge else 0
 
         # ---- every record on its own: before each wave the rings hold the oracle's state ----
-        worst_step = strict_step = 0.0
+        worst_step = strict_step = worst_excess = 0.0
         if per_wave_check:
             sess.set_params(p0)
             rings = arith.init_rings(p0.numpy(), N, h.D)
@@ -160,45 +225,63 @@ def run_parity(c, per_wave_check=True):
                           for e in members if has_hinge and recs[e].kind == protocol.STEP}
                 after = sess.ring_snapshot()
                 vel_after = sess.vel_snapshot() if mu > 0 else None
-                grad = FollowKernelAtTies(base, active, scale_of) if has_hinge else base
+                grad = KeepGradient(FollowKernelAtTies(base, active, scale_of) if has_hinge else base)
                 for e in members:         # members of a wave touch no slot in a conflicting way
                     r = recs[e]
+                    vecs = [rings[j, sl].copy() for j, sl in zip(r.src_worker, r.src_slot)]
+                    vel_before = vel[r.worker].copy() if mu > 0 and r.kind == protocol.STEP else None
+                    grad.last = None
                     ref = arith.apply_record(rings, r, grad, c["lr"], vel, mu)
-                    worst_step = max(worst_step, rel_err(after[r.worker, r.out_slot], ref))
-                    strict_step = max(strict_step, strict_rel_err(after[r.worker, r.out_slot], ref))
+                    got_vec = after[r.worker, r.out_slot]
+                    mag, n_terms, extra = record_terms(c, data_np, base, r, vecs, grad.last, vel_before, mu, scale_of)
+                    excess = forward_excess(got_vec, ref, mag, n_terms, extra)
+                    assert excess <= 1.0, (e, r.kind, r.worker, r.k, excess)
+                    worst_excess = max(worst_excess, excess)
+                    worst_step = max(worst_step, rel_err(got_vec, ref))
+                    strict_step = max(strict_step, strict_rel_err(got_vec, ref))
                     if mu > 0 and r.kind == protocol.STEP and c["model"] != "none":
                         worst_step = max(worst_step, rel_err(vel_after[r.worker], vel[r.worker]))
-                flips += grad.flips if has_hinge else 0
+                flips += grad.inner.flips if has_hinge else 0
             assert worst_step <= STEP_TOL, worst_step
-        print("  records %d waves %d jumps %d  per-record err %.2e (floor 1e-3 rms: %.2e)  end-of-run err "
-              "%.2e (floor 1e-3 rms: %.2e)  ties followed %d"
-              % (len(recs), sched.n_waves, sched.n_jumps, worst_step, strict_step, worst_run, strict_run, flips),
-              flush=True)
+            if strict:
+                assert strict_step <= STEP_TOL, strict_step
+        print("  records %d waves %d jumps %d  per-record: rounding bound used %.2f, err %.2e (floor 1e-3 rms: %.2e)  "
+              "end of run: err %.2e (floor 1e-3 rms: %.2e)  ties followed %d"
+              % (len(recs), sched.n_waves, sched.n_jumps, worst_excess, worst_step, strict_step, worst_run, strict_run,
+                 flips), flush=True)
         assert worst_run <= RUN_TOL, worst_run
+        if strict:
+            assert strict_run <= (RUN_TOL if strict_run_tol is None else strict_run_tol), strict_run
         return worst_step, worst_run
     finally:
         sess.close()
 
 
 def test_cfg1_ring4_dense_full_size():
-    run_parity(inputs.config(1))
+    run_parity(inputs.config(1), strict=True)
 
 
 def test_cfg2_ring16_dense_reduced():
-    run_parity(inputs.config(2, d=8192 + 4, rows=512, K=40))
+    run_parity(inputs.config(2, d=8192 + 4, rows=512, K=40), strict=True)
 
 
 def test_cfg3_torus16_csr_reduced():
-    run_parity(inputs.config(3, d=1 << 14, rows=2048, K=40))
+    run_parity(inputs.config(3, d=1 << 14, rows=2048, K=40), strict=True)
 
 
 def test_cfg4_chords32_mix_reduced():
-    run_parity(inputs.config(4, d=(1 << 15) + 3, K=100), per_wave_check=False)
-    run_parity(inputs.config(4, d=4096, K=30))
+    run_parity(inputs.config(4, d=(1 << 15) + 3, K=100), per_wave_check=False, strict=True)
+    run_parity(inputs.config(4, d=4096, K=30), strict=True)
 
 
 def test_cfg5_torus64_csr_reduced():
-    run_parity(inputs.config(5, d=1 << 13, rows=1024, K=24))
+    """End of run against the 1e-3 rms floor: this workload sits AT fp32's resolution there.  Zipf columns put
+    most of a replica's norm into a few hot entries, every update adds terms of that size to entries a thousand
+    times smaller, and one fp32 rounding of an rms-sized term is 2^-24 / 1e-3 = 6e-5 of the floor.  The figure
+    moves between 6e-5 and 2e-4 from run to run (the scatter's atomics have no fixed order; measured at
+    d = 2^13, 2^14, 2^15), so it is held to four such roundings; per record, and against the rms floor, the
+    bars are the usual ones."""
+    run_parity(inputs.config(5, d=1 << 13, rows=1024, K=24), strict=True, strict_run_tol=4 * 2.0 ** -24 / 1e-3)
 
 
 @pytest.mark.parametrize("s,b,skip,ig", [(0, 0, False, 0), (0, 1, True, 3), (2, 1, True, 4), (3, 0, False, 0)])
@@ -266,8 +349,8 @@ def test_cfg4_full_size_sampled_columns():
         want = arith.final_params(rings, ver)
         assert its == ver
         idx = torch.from_numpy(cols).to(sess.dev)
-        worst = max(rel_err(got[i][idx].cpu().numpy(), want[i]) for i in range(c["N"]))
-        print("  end-of-run err on %d sampled columns: %.2e" % (len(cols), worst), flush=True)
+        worst = max(strict_rel_err(got[i][idx].cpu().numpy(), want[i]) for i in range(c["N"]))
+        print("  end-of-run err on %d sampled columns (floor 1e-3 rms): %.2e" % (len(cols), worst), flush=True)
         assert worst <= RUN_TOL
     finally:
         sess.close()
@@ -383,7 +466,7 @@ def test_full_size_first_records(cfgn, n_records):
             w += 1
         print("  %d records in %d waves: per-record err %.2e (floor 1e-3 rms: %.2e)" % (done, w, worst, strict),
               flush=True)
-        assert done >= n_records and worst <= STEP_TOL
+        assert done >= n_records and worst <= STEP_TOL and strict <= STEP_TOL
     finally:
         sess.close()
 
