@@ -42,35 +42,83 @@ def read_traffic(name):
         return None
 
 
-def cpu_baseline(c, recs, p0, budget_s=20.0):
-    """The oracle as it stands, timed on this host on the first records of the same schedule at
-    full d.  Rings are built lazily (every slot 0 is p0) so the sample needs no 16 GB of host RAM."""
+def _oracle_slice(args):
+    """The oracle's Reduce + Apply on the columns [lo, hi) of the first `n_records` STEP records (all of the
+    method's arithmetic is separable by column, and the synthetic gradient can be generated per column)."""
     import numpy as np
 
     from oracle import arith
-    p0n = p0.cpu().numpy()
+    c, recs, p0n, lo, hi, n_records = args
+    p0s = p0n[lo:hi]
     slots = {}
 
     def get(j, sl):
         if (j, sl) in slots:
             return slots[(j, sl)]
-        assert sl == 0, "sample reaches past the first versions"
-        return p0n
-    grad = arith.GradSynth(c["seed"], c["grad_var"], np.arange(c["d"])) if c["model"] == "synth" else None
-    done, t0 = 0, time.perf_counter()
+        assert sl == 0, "sample reaches past the versions it has produced"
+        return p0s
+    grad = arith.GradSynth(c["seed"], c["grad_var"], np.arange(lo, hi))
+    done = 0
     for r in recs:
         if r.kind != 0:
             continue
         vecs = [get(j, sl) for j, sl in zip(r.src_worker, r.src_slot)]
-        g = grad(r.worker, r.k, vecs[0]) if grad is not None else None
-        slots[(r.worker, r.out_slot)] = arith.reduce_apply(vecs, r.w32, g, c["lr"])
+        slots[(r.worker, r.out_slot)] = arith.reduce_apply(vecs, r.w32, grad(r.worker, r.k, vecs[0]), c["lr"])
         done += 1
-        if time.perf_counter() - t0 > budget_s or done >= 28:
+        if done >= n_records:
             break
-    dt = time.perf_counter() - t0
-    return {"value": done / dt, "unit": "worker-updates/s", "cores": 1, "kind": "oracle",
-            "sample": "first %d STEP records of the same schedule at full d=%d (numpy, fp64 accumulate), %.1f s"
-                      % (done, c["d"], dt)}
+    return done
+
+
+def cpu_baseline(c, recs, p0):
+    """The oracle as it stands (numpy, fp64 accumulation), timed on this host on the first STEP records of the
+    same schedule at full d: on one core, then with the columns split over all the cores this process may use
+    (at most 16, a one-GPU machine's share).  Runs before anything touches the GPU, so the worker processes can be
+    plain forks."""
+    import multiprocessing as mp
+
+    p0n = p0.numpy()
+    d = c["d"]
+    t0 = time.perf_counter()
+    one = _oracle_slice((c, recs, p0n, 0, d, 12))
+    t_one = time.perf_counter() - t0
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    cores = max(1, min(avail, 16))
+    n_all = 64
+    bounds = [d * q // cores for q in range(cores + 1)]
+    with mp.get_context("fork").Pool(cores) as pool:
+        pool.map(_oracle_slice, [(c, recs, p0n, 0, 1024, 1)] * cores)          # start the workers before the clock
+        t0 = time.perf_counter()
+        done = pool.map(_oracle_slice, [(c, recs, p0n, bounds[q], bounds[q + 1], n_all) for q in range(cores)])
+        t_all = time.perf_counter() - t0
+    return {"value": done[0] / t_all, "unit": "worker-updates/s", "cores": cores, "kind": "oracle",
+            "one_core_value": one / t_one, "host_cpu_count": os.cpu_count(),
+            "sample": "first %d STEP records of the same schedule at full d=%d, columns split over %d processes, "
+                      "%.1f s; one core: first %d records, %.1f s (numpy, fp64 accumulation)"
+                      % (done[0], d, cores, t_all, one, t_one)}
+
+
+def wave_compulsory_bytes(sched, d, mode, momentum):
+    """HBM bytes one Reduce + Apply launch cannot avoid, per wave, from the schedule itself: every distinct
+    (worker, slot) vector the wave reads once, one result per record, one gradient per STEP record where the
+    kernel reads a dense one (synthetic, external, large dense minibatches), the velocity read and written."""
+    import numpy as np
+    out = np.zeros(int(sched.n_waves))
+    for w in range(int(sched.n_waves)):
+        members = sched.wave_order[sched.wave_begin[w]:sched.wave_begin[w + 1]]
+        srcs = set()
+        vectors = 0
+        for e in members:
+            a0, a1 = int(sched.src_begin[e]), int(sched.src_begin[e + 1])
+            srcs.update(zip(sched.src_worker[a0:a1].tolist(), sched.src_slot[a0:a1].tolist()))
+            vectors += 1
+            if sched.kind[e] == 0 and mode in ("synth", "dense_g"):
+                vectors += 1 + (2 if momentum else 0)
+        out[w] = 4.0 * d * (len(srcs) + vectors)
+    return out
 
 
 def run_config(cfgn, steps, warmup, graph, over=None):
@@ -93,6 +141,8 @@ def run_config(cfgn, steps, warmup, graph, over=None):
             hop.hop_set_grad_source(sess.ctx, hop.HOP_GRAD_SYNTH, c["grad_var"])
         sess.set_params(p0)
         sched = sess.simulate()
+        mix_mode = "synth" if c["model"] == "synth" else ("dense_g" if c["model"] == "dense" and c["batch"] * c["d"] * 4 > (2 << 20) else "none")
+        compulsory = wave_compulsory_bytes(sched, c["d"], mix_mode, c.get("momentum", 0.0) > 0)
         n_step = int((sched.kind == hop.HOP_STEP).sum())
         n_jump = int((sched.kind == hop.HOP_JUMP).sum())
         A = (sched.src_begin[1:] - sched.src_begin[:-1])
@@ -134,7 +184,9 @@ def run_config(cfgn, steps, warmup, graph, over=None):
                 "step_definition": "one pass of hop_step over the whole schedule",
                 "launch": "hip graph replay" if graph else "kernel by kernel",
             },
-            "mix": {"ms": mix_ms, "launches": int(mix_n), "bytes": mix_bytes, "GBps": rate(mix_bytes, mix_ms)},
+            "mix": {"ms": mix_ms, "launches": int(mix_n), "bytes": mix_bytes, "GBps": rate(mix_bytes, mix_ms),
+                    "compulsory_bytes_per_pass": float(compulsory.sum()),
+                    "passes_timed": int(mix_n) // max(int(sched.n_waves), 1)},
             "grad": {"ms": grad_ms, "launches": int(grad_n), "GBps": rate(grad_bytes, grad_ms)},
             "synth": {"ms": syn_ms, "launches": int(syn_n), "GBps": rate(syn_bytes, syn_ms)},
         }
@@ -185,8 +237,31 @@ def main():
         over["loss"] = 1
     if args.seed:
         over["seed"] = args.seed
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle first, while no GPU runtime is alive in this process (its all-cores leg forks workers)
+        from oracle import protocol
+        from paper_1902_01064_amd import inputs
+        c0 = inputs.config(args.config, **over)
+        if c0["model"] == "synth" and not args.momentum:
+            h = protocol.Hop(c0["in_nbrs"], c0["W"], c0["s"], c0["b"], c0["K"], max_ig=c0["max_ig"],
+                             skip_on=c0["skip_on"], max_skip=c0["max_skip"], trigger=c0["trigger"], seed=c0["seed"],
+                             delay_kind=c0["delay_kind"], mult=c0["mult"], check=False)
+            cpu = cpu_baseline(c0, h.run(), inputs.initial_params(c0["seed"], c0["d"], 0.01))
     res, c, p0 = run_config(args.config, args.steps, args.warmup, args.graph, over or None)
+    del p0
     mix = res["mix"]
+    launches = max(mix["launches"], 1)
+    avg_us = mix["ms"] * 1e3 / launches
+    compulsory = mix["compulsory_bytes_per_pass"] * mix["passes_timed"] / launches      # per launch
+    hbm_GBps = compulsory / (avg_us * 1e-6) / 1e9 if avg_us > 0 else 0.0
+    counters = None if over else read_traffic("hop_mix_cfg%d_traffic.txt" % args.config)
+    note = None
+    if counters is not None and abs(counters - compulsory) > 0.03 * compulsory:
+        note = ("profiles/hop_mix_cfg%d_traffic.txt holds %.4g bytes per launch, the schedule of this run needs %.4g: "
+                "the counter figure belongs to another schedule or kernel and is not quoted"
+                % (args.config, counters, compulsory))
+        counters = None
     out = {
         "metric": METRIC,
         "value": res["value"],
@@ -201,40 +276,47 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": res["config"],
+        # HBM side: the bytes a launch cannot avoid (every distinct source of the wave once, one gradient and one
+        # result per record; from this run's schedule) over the launch time measured in this run.  The rate at which
+        # the records' 4 d (A + 2) bytes reach the CUs is higher (sources shared through L2) and is no HBM figure.
         "roofline": {
-            "bound": "hbm", "kernel": "mix_kernel", "achieved": mix["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": mix["GBps"] / HBM_PEAK_GBS,
-            "traffic": None if over else read_traffic("hop_mix_cfg%d_traffic.txt" % args.config),
-            "launches": mix["launches"], "avg_launch_us": mix["ms"] * 1e3 / max(mix["launches"], 1),
-            "algorithmic_bytes_per_launch": mix["bytes"] / max(mix["launches"], 1),
+            "bound": "hbm", "kernel": "pair_mix_kernel", "achieved": hbm_GBps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": hbm_GBps / HBM_PEAK_GBS,
+            "traffic": counters,
+            "launches": mix["launches"], "avg_launch_us": avg_us,
+            "compulsory_bytes_per_launch": compulsory,
+            "algorithmic_bytes_per_launch": mix["bytes"] / launches,
+            "l2_side_GBps": mix["GBps"],
         },
-        "kernels": {k: {kk: vv for kk, vv in res[k].items() if kk != "bytes"} for k in ("mix", "grad", "synth")},
+        "kernels": {k: {kk: vv for kk, vv in res[k].items() if kk not in ("bytes", "compulsory_bytes_per_pass", "passes_timed")}
+                    for k in ("mix", "grad", "synth")},
     }
     r = out["roofline"]
-    if r["traffic"] and r["avg_launch_us"] > 0:
-        # the same launches seen from the HBM side: counter bytes over the measured duration
-        r["traffic_GBps"] = r["traffic"] / (r["avg_launch_us"] * 1e-6) / 1e9
+    if note:
+        r["traffic_note"] = note
+    if counters and avg_us > 0:
+        r["traffic_GBps"] = counters / (avg_us * 1e-6) / 1e9
         r["traffic_frac"] = r["traffic_GBps"] / HBM_PEAK_GBS
     if not args.no_cpu_baseline:
-        from oracle import protocol
-        if c["model"] == "synth" and not args.momentum:
-            h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], c["K"], max_ig=c["max_ig"],
-                             skip_on=c["skip_on"], max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
-                             delay_kind=c["delay_kind"], mult=c["mult"], check=False)
-            out["cpu_baseline"] = cpu_baseline(c, h.run(), p0)
-        else:
-            out["cpu_baseline"] = None
-    del p0
+        out["cpu_baseline"] = cpu
     if not args.no_others and not over:
         others = {}
+        bound = {1: "launches (80 KB per wave)", 2: "gradient: hbm; Reduce: launches (6.5 records of 256 KB per wave)",
+                 3: "launches (3.4 records of 4 MB per wave)", 4: "hbm", 5: "hbm"}
         for n in (1, 2, 3, 5):
             if n == args.config:
                 continue
             r, _, _ = run_config(n, 2, 1, True)
+            m = r["mix"]
+            passes = max(m["passes_timed"], 1)
+            n_launch = (m["launches"] + r["grad"]["launches"] + r["synth"]["launches"]) / passes
             others[r["config"]["workload"]] = {
                 "worker_updates_per_s": r["value"], "ms_per_step": r["ms_per_step"], "launch": r["config"]["launch"],
                 "records": r["config"]["step_records"] + r["config"]["jump_records"], "waves": r["config"]["waves"],
-                "mix_GBps": r["mix"]["GBps"], "grad_GBps": r["grad"]["GBps"]}
+                "timed_kernel_groups_per_pass": n_launch, "bound": bound[n],
+                "mix_l2_side_GBps": m["GBps"],
+                "mix_hbm_GBps": m["compulsory_bytes_per_pass"] * passes / (m["ms"] * 1e-3) / 1e9 if m["ms"] > 0 else 0.0,
+                "grad_GBps": r["grad"]["GBps"]}
         out["other_configs"] = others
     print(json.dumps(out))
 

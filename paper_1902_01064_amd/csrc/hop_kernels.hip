@@ -426,8 +426,11 @@ __device__ __forceinline__ void pair_block(const HopPairJob* __restrict__ jobs, 
     const int sub = (int)(local % run);
     const int j = (int)((local / run) % n_jobs);
     const int64_t round = local / ((int64_t)run * n_jobs);
-    const int64_t chunk = (round * kXcd + xcd) * run + sub;
-    if (chunk >= n_chunks) return;
+    const int64_t ahead = (round * kXcd + xcd) * run + sub;
+    if (ahead >= n_chunks) return;
+    // vectors are walked from their end: the kernel that wrote the wave's gradients went through them from
+    // the start, so what it wrote last is still in the memory-side cache when this one begins
+    const int64_t chunk = n_chunks - 1 - ahead;
     const HopPairJob* job = jobs + j;
     const int64_t n4 = d >> 2;
     const int64_t first4 = chunk * (int64_t)(kThreads * kPairVec);
