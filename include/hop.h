@@ -285,6 +285,18 @@ int64_t hop_grad_scratch_floats(int64_t d, int32_t B);
 int hop_svm_grad_dense(const float* X, const float* y, const float* w, const int32_t* rows_dev,
                        int32_t B, int64_t d, float lambda, int32_t loss, float* g, float* coef,
                        float* scratch, void* hip_stream);
+/* The same gradient for callers that cannot allocate device memory - a stream under graph capture, a tight
+ * serving loop, a harness that forbids hipMalloc.  Same arguments and results as hop_svm_grad_dense without
+ * the scratch argument: the descriptor and the partial dot products live in a fixed array of device memory
+ * inside the library (256 KB + 256 B per GPU, held until the process ends), and the call only enqueues three
+ * kernels on the stream and returns (no allocation, no copy, no wait: the caller synchronises).  Limit:
+ * B x ceil(d / 16384) <= 65536, else HOP_ERR_ARENA_TOO_SMALL and nothing is launched.  All calls on one GPU
+ * share that array: calls whose kernels could overlap (different streams, or a captured graph replayed
+ * beside another call) race and must be ordered by the caller.  Nothing in the array needs clearing between
+ * calls: every partial sum a call reads was written by the same call. */
+int hop_svm_grad_dense_static(const float* X, const float* y, const float* w, const int32_t* rows_dev,
+                              int32_t B, int64_t d, float lambda, int32_t loss, float* g, float* coef,
+                              void* hip_stream);
 /* Same on CSR features; g (device, d floats) receives the dense gradient. */
 int hop_svm_grad_csr(const int64_t* rowptr, const int32_t* col, const float* val, const float* y,
                      const float* w, const int32_t* rows_dev, int32_t B, int64_t d, float lambda,

@@ -4,7 +4,9 @@
 // the work is coalesced 128-bit streaming, wavefront reductions and LDS staging of small tables.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
+#include <cstring>
 
 #include "hop_internal.h"
 
@@ -1063,4 +1065,68 @@ int hopk_copy(void* dst, const void* src, size_t bytes, void* stream) {
     hipLaunchKernelGGL(copy_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, (float4*)dst,
                        (const float4*)src, n16);
     return launch_status();
+}
+
+// ------------------------------------------- dense SVM gradient without any allocation ----
+// For callers that cannot allocate (a stream being captured, a tight serving loop, a harness that forbids
+// hipMalloc): the job descriptor and the partial dot products, which hop_svm_grad_dense takes from a hipMalloc
+// of its own and from the caller's scratch argument, live in a fixed array in device memory instead.
+namespace {
+
+constexpr size_t kStaticDescBytes = 256;
+constexpr int64_t kStaticPartials = 65536;                 // most B x column segments (16384 columns each)
+static __device__ __align__(256) unsigned char scratch[kStaticDescBytes + kStaticPartials * sizeof(float)];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];                          // device address of `scratch` on each GPU, once known
+int g_scratch_state[kMaxDevices];                          // 0 unknown, 1 known
+
+__global__ void stage_job_kernel(HopGradJob job, HopGradJob* dst) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *dst = job;
+}
+
+}  // namespace
+
+extern "C" int hop_svm_grad_dense_static(const float* X, const float* y, const float* w, const int32_t* rows_dev,
+                                         int32_t B, int64_t d, float lambda, int32_t loss, float* g, float* coef,
+                                         void* hip_stream) {
+    if (!X || !y || !w || !rows_dev || !g || !coef || B < 1 || B > kMaxB || d < 1 ||
+        (loss != HOP_LOSS_HINGE && loss != HOP_LOSS_LOG))
+        return HOP_ERR_INVALID_ARG;
+    if (d % 4 == 0 && ((((uintptr_t)X | (uintptr_t)w | (uintptr_t)g) & 15u) != 0)) return HOP_ERR_INVALID_ARG;
+    const int nseg = hopk_dense_nseg(d);
+    if ((int64_t)B * nseg > kStaticPartials) {
+        fprintf(stderr, "libhop: hop_svm_grad_dense_static: B x ceil(d / 16384) = %lld exceeds the fixed scratch of %lld "
+                        "partial sums\n", (long long)B * nseg, (long long)kStaticPartials);
+        return HOP_ERR_ARENA_TOO_SMALL;
+    }
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HOP_ERR_HIP;
+    if (!g_scratch_state[dev]) {
+        // each GPU holds its own copy of the array at its own address: ask once per device, with it current
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) {
+            fprintf(stderr, "libhop: hipGetSymbolAddress(scratch): %s\n", hipGetErrorString(e));
+            return HOP_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+        g_scratch_state[dev] = 1;
+    }
+    unsigned char* base = (unsigned char*)g_scratch_ptr[dev];
+    HopGradJob* desc = (HopGradJob*)base;
+    static_assert(sizeof(HopGradJob) <= kStaticDescBytes, "descriptor must fit its slot");
+    HopGradJob gj;
+    memset(&gj, 0, sizeof(gj));
+    gj.X = X; gj.y = y; gj.w = w; gj.rows = rows_dev; gj.g = g; gj.coef = coef;
+    gj.partial = (float*)(base + kStaticDescBytes);        // every entry is written by the margin pass before it is read
+    hipLaunchKernelGGL(stage_job_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, gj, desc);
+    int rc = launch_status();
+    if (!rc) rc = hopk_dense_margin(desc, 1, B, d, hip_stream);
+    if (!rc) rc = hopk_dense_grad(desc, 1, B, d, lambda, loss, hip_stream);
+    if (rc) {
+        fprintf(stderr, "libhop: hop_svm_grad_dense_static launch: %s\n", hipGetErrorString((hipError_t)rc));
+        return HOP_ERR_HIP;
+    }
+    return HOP_OK;
 }

@@ -30,6 +30,7 @@ EXPORTS = [
     "hop_params", "hop_slot", "hop_coef", "hop_profile", "hop_profile_read", "hop_mix",
     "hop_grad_scratch_floats", "hop_svm_grad_dense", "hop_svm_grad_csr", "hop_synth_grad", "hop_copy",
     "hop_download", "hop_use_graph", "hop_schedule_bytes", "hop_schedule_bind",
+    "hop_svm_grad_dense_static",
 ]
 
 
@@ -127,6 +128,7 @@ def load():
         "hop_mix": (C.c_int, [C.POINTER(hop_mix_job), i32, i64, vp]),
         "hop_grad_scratch_floats": (i64, [i64, i32]),
         "hop_svm_grad_dense": (C.c_int, [vp, vp, vp, vp, i32, i64, f32, i32, vp, vp, vp, vp]),
+        "hop_svm_grad_dense_static": (C.c_int, [vp, vp, vp, vp, i32, i64, f32, i32, vp, vp, vp]),
         "hop_svm_grad_csr": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i64, f32, i32, vp, vp, vp]),
         "hop_synth_grad": (C.c_int, [C.c_uint64, i32, i32, f32, vp, i64, vp]),
         "hop_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
@@ -355,6 +357,11 @@ def hop_grad_scratch_floats(d, B):
 def hop_svm_grad_dense(X, y, w, rows, B, d, lam, g, coef, scratch, stream=0, loss=HOP_LOSS_HINGE):
     _check(load().hop_svm_grad_dense(X, y, w, rows, B, d, lam, loss, g, coef, scratch, C.c_void_p(stream)),
            "hop_svm_grad_dense")
+
+
+def hop_svm_grad_dense_static(X, y, w, rows, B, d, lam, g, coef, stream=0, loss=HOP_LOSS_HINGE):
+    _check(load().hop_svm_grad_dense_static(X, y, w, rows, B, d, lam, loss, g, coef, C.c_void_p(stream)),
+           "hop_svm_grad_dense_static")
 
 
 def hop_svm_grad_csr(rowptr, col, val, y, w, rows, B, d, lam, g, coef, stream=0, loss=HOP_LOSS_HINGE):
