@@ -367,9 +367,9 @@ def test_skipping_worked_examples(which):
 
 
 def test_backup_example_state_of_the_figure():
-    """Section 3.4: "worker A is stuck at iteration 0, while worker B and C are able to advance to
-    iteration 3 and 4": with one update needed, C (faster) runs one iteration ahead of B and never
-    more, since it needs B's update of the same iteration."""
+    """Section 3.4, backup-worker example: state (0, 3, 4) - A stuck at iteration 0, B at 3, C at 4.  With one
+    update needed, C (faster) runs one iteration ahead of B and never more, since it needs B's update of the
+    same iteration."""
     nb = inputs.complete(3)
     h = run(nb, 0, 1, 12, max_ig=20, mult=[NEVER, 1.0, 0.5], trace=True)
     it, states = [0, 0, 0], set()
