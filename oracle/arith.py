@@ -19,6 +19,9 @@ TEST INFRASTRUCTURE ONLY - see oracle/__init__.py.
                    velocity is never sent or averaged; a jump leaves it alone)
   reduce_apply     x_{k+1,i} = sum_a w'_a x_a - eta g   (steps 2 and 3 there)
   execute          all records in sequence order over rings of D slots
+                   (serial approach of Section 3.2: an APPLY record is the same formula with the
+                   single source x_k and weight 1, y_k = x_k - eta g(x_k); a REDUCE record the
+                   same without gradient, x_{k+1} = sum_a w'_a y_a; x_k lives in slot D)
 
 State and weights are fp32 (what is stored), sums are carried in fp64.
 """
@@ -28,6 +31,8 @@ from . import rng
 
 STEP = 0
 JUMP = 1
+APPLY = 2
+REDUCE = 3
 
 
 def reduce_weights(W, i, k, s, src_worker, src_tag):
@@ -147,12 +152,13 @@ class GradSvmCsr:
         return g
 
 
-def init_rings(p0, N, D):
-    """x_{0,i} = p_0 in slot 0 of every worker (p0: [d] shared, or [N, d])."""
+def init_rings(p0, N, D, serial=False):
+    """x_{0,i} = p_0 in slot 0 of every worker (p0: [d] shared, or [N, d]).  D counts the slots in
+    memory; with the serial approach the last of them holds the current parameters, and x_0 goes there."""
     p0 = np.asarray(p0, dtype=np.float32)
     rings = np.zeros((N, D) + p0.shape[-1:], dtype=np.float32)
     for i in range(N):
-        rings[i, 0] = p0 if p0.ndim == 1 else p0[i]
+        rings[i, D - 1 if serial else 0] = p0 if p0.ndim == 1 else p0[i]
     return rings
 
 
@@ -170,7 +176,7 @@ def apply_record(rings, rec, grad, eta, vel=None, mu=0.0):
     velocities (updated in place by STEP records) when momentum is on."""
     vecs = [rings[j, sl] for j, sl in zip(rec.src_worker, rec.src_slot)]
     g = None
-    if rec.kind == STEP:
+    if rec.kind == STEP or rec.kind == APPLY:
         g = grad(rec.worker, rec.k, vecs[0])
         if vel is not None:
             g, vel[rec.worker] = momentum_step(vel[rec.worker], g, mu)
@@ -184,12 +190,19 @@ def execute(records, rings, grad, eta, on_record=None, vel=None, mu=0.0):
     version = [0] * rings.shape[0]
     for rec in records:
         out = apply_record(rings, rec, grad, eta, vel, mu)
-        version[rec.worker] = rec.k + 1 if rec.kind == STEP else rec.k
+        if rec.kind == STEP or rec.kind == REDUCE:
+            version[rec.worker] = rec.k + 1
+        elif rec.kind == JUMP:
+            version[rec.worker] = rec.k
         if on_record is not None:
             on_record(rec, out)
     return version
 
 
-def final_params(rings, version):
+def final_params(rings, version, serial=False):
+    """Newest parameters of every worker: ring slot version mod D, or - serial approach, whose rings
+    carry one more slot per worker - the current-parameter slot."""
+    if serial:
+        return np.stack([rings[i, rings.shape[1] - 1] for i in range(rings.shape[0])])
     D = rings.shape[1]
     return np.stack([rings[i, version[i] % D] for i in range(rings.shape[0])])

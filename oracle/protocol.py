@@ -48,6 +48,27 @@ the repository's design notes):
     send what the receiver is already past) is kept as a counter, late_sends:
     in exact-tag mode such an update is always dropped at the next dequeue.
 
+Two more options complete the design space of Sections 3.2 and 3.3 (comparison only; the paper's
+own design is the parallel approach with token queues):
+  - serial=True: the serial approach of Section 3.2.  On entering iteration k a worker Computes
+    on its current parameters x_k, Applies (y_k = x_k - eta g), and only then Sends y_k; when
+    Recv(k) is satisfied it Reduces the y's (its own included) into x_{k+1}.  Two records per
+    iteration: APPLY (x_cur, gradient -> ring slot k mod D, the vector that is sent) and REDUCE
+    (ring slots -> x_cur).  x_cur is a slot of its own per worker (index D), never sent.  With
+    s = 0, b = 0 this is X_{k+1} = W^T (X_k - eta G_k) whatever the delays.  The queue rules
+    (tokens, backup workers, staleness, skipping) are the same; a jump's Reduce reads and
+    writes x_cur.
+  - notify_ack=True: the NOTIFY-ACK protocol of Section 3.3 on the parallel approach, standard
+    training only (s = 0, no backup workers, no skipping, no token queues - Section 3.3 and
+    the introduction say it supports none of them).  A worker may not Send(k) before every
+    out-going neighbour has acknowledged its update of iteration k - 1; a worker acknowledges
+    to all in-coming neighbours right after the Reduce that consumed their updates; Recv and
+    Reduce of iteration k run as soon as the updates of iteration k are all there, beside the
+    Compute (that is what the parallel approach allows, and what lets a sender get 2 ahead of
+    a receiver, the table's figure); the worker advances when it has computed, sent and
+    received (the Assumption of Section 3.3).  An acknowledgement travels one tick.  Records
+    are those of standard training; only times and order change.  Ring as for max_ig = 2.
+
 Versions live in a ring of D slots per worker, slot = version mod D, with
 D = max_ig + 1 in staleness mode (the paper's #queues) and max_ig + 2 in
 exact-tag mode (the ring also holds the not yet sent x_{k+1}).  With
@@ -63,11 +84,14 @@ import numpy as np
 from . import rng
 from .arith import reduce_weights
 
-STEP = 0
-JUMP = 1
+STEP = 0      # parallel approach: Reduce + Apply of one iteration
+JUMP = 1      # Section 5: Reduce without gradient into the iteration jumped to
+APPLY = 2     # serial approach: y_k = x_k - eta g(x_k) into the ring slot that is sent
+REDUCE = 3    # serial approach: x_{k+1} = sum_a w'_a y_a into the worker's current parameters
 
 EV_ARRIVE = 0
 EV_DONE = 1
+EV_ACK = 2
 
 COMPUTING = 0
 WAIT_RECV = 1
@@ -130,7 +154,7 @@ class Hop:
 
     def __init__(self, in_nbrs, W, s, b, K, max_ig=0, skip_on=False, max_skip=10,
                  trigger=1, seed=0, delay_kind=rng.DELAY_NONE, mult=None,
-                 table=None, check=True, trace=False, max_latency=1):
+                 table=None, check=True, trace=False, max_latency=1, serial=False, notify_ack=False):
         self.N = len(in_nbrs)
         self.in_nbrs = [sorted(l) for l in in_nbrs]
         self.out_nbrs = transpose(self.in_nbrs)
@@ -142,7 +166,13 @@ class Hop:
         self.mult = [1.0] * self.N if mult is None else [float(m) for m in mult]
         self.table = table
         self.max_latency = int(max_latency)
+        self.serial, self.notify_ack = bool(serial), bool(notify_ack)
+        if self.notify_ack:
+            if self.s != 0 or self.b != 0 or self.skip_on or self.serial or self.max_latency > 1:
+                raise ProtocolError("NOTIFY-ACK is standard training on the parallel approach only")
+            self.max_ig = 2                      # a sender is never more than 2 ahead: ring as for max_ig = 2
         self.D = ring_depth(self.s, self.max_ig, self.max_latency)
+        self.slots = self.D + (1 if self.serial else 0)     # slots per worker in memory; slot D = x_cur (serial)
         self.check = check
         for i in range(self.N):
             if self.b > 0 and self.b >= len(self.in_nbrs[i]):
@@ -202,6 +232,13 @@ class Hop:
         self.records.append(r)
 
     # ---- iteration boundaries -------------------------------------------------
+    def _send(self, i, k, T):
+        for j in self.out_nbrs[i]:
+            lat = rng.latency_ticks(self.seed, self.max_latency, i, j, k)
+            heapq.heappush(self.events, (T + lat, EV_ARRIVE, j, i, k))
+            if self.Iter[j] > k:
+                self.late_sends += 1
+
     def _enter(self, i, k, T):
         self.Iter[i] = k
         for j in self.in_nbrs[i]:
@@ -212,11 +249,8 @@ class Hop:
             self.state[i] = FINISHED
             self.finish_time[i] = T
         else:
-            for j in self.out_nbrs[i]:
-                lat = rng.latency_ticks(self.seed, self.max_latency, i, j, k)
-                heapq.heappush(self.events, (T + lat, EV_ARRIVE, j, i, k))
-                if self.Iter[j] > k:
-                    self.late_sends += 1
+            if not self.serial:
+                self._send(i, k, T)              # parallel approach: Send x_k on entering iteration k
             dur = rng.duration_ticks(self.seed, self.delay_kind, self.N, self.mult[i], i, k,
                                      self.table)
             if dur < rng.TICKS_NEVER:
@@ -239,8 +273,12 @@ class Hop:
             return
         self._recv_commit(i, k)
         D = self.D
-        self._emit(STEP, i, k, k, k % D, accepted, (k + 1) % D, T)
-        self.written[i] = k + 1
+        if self.serial:
+            # Reduce of the sent vectors (own y_k in ring slot k mod D) into the current parameters
+            self._emit(REDUCE, i, k, k, k % D, accepted, D, T)
+        else:
+            self._emit(STEP, i, k, k, k % D, accepted, (k + 1) % D, T)
+            self.written[i] = k + 1
         if self.trace is not None:
             self.trace.append(("recv", i, k, tuple(accepted)))
         k0 = k
@@ -253,8 +291,11 @@ class Hop:
                     ok2, acc2 = self._recv_eval(i, kp - 1)
                     if ok2:
                         self._recv_commit(i, kp - 1)
-                        self._emit(JUMP, i, kp - 1, kp, (k0 + 1) % D, acc2, kp % D, T)
-                        self.written[i] = kp
+                        if self.serial:          # x_cur (= x_{k0+1}) renewed in place
+                            self._emit(JUMP, i, kp - 1, kp, D, acc2, D, T)
+                        else:
+                            self._emit(JUMP, i, kp - 1, kp, (k0 + 1) % D, acc2, kp % D, T)
+                            self.written[i] = kp
                         for j in self.out_nbrs[i]:
                             self.tokens[(j, i)] -= J
                             assert self.tokens[(j, i)] >= 0
@@ -310,6 +351,8 @@ class Hop:
         self.late_sends = 0
         self.max_gap = 0
         self.max_queue = 0
+        if self.notify_ack:
+            return self._run_notify_ack()
         for i in range(N):
             self._enter(i, 0, 0)
         if self.check:
@@ -325,9 +368,99 @@ class Hop:
                     self._try_recv(a, T)
             else:
                 assert self.state[a] == COMPUTING and self.Iter[a] == tag
+                if self.serial:
+                    # Apply, then Send: y_k = x_k - eta g(x_k) goes into ring slot k mod D and out
+                    self._emit(APPLY, a, tag, tag, self.D, [], tag % self.D, T)
+                    self.written[a] = tag
+                    self._send(a, tag, T)
                 self.state[a] = WAIT_RECV
                 self._try_recv(a, T)
             if self.check:
                 self._check()
+        self.stalled = any(st != FINISHED for st in self.state)
+        return self.records
+
+    # ---- NOTIFY-ACK (Section 3.3) ------------------------------------------------
+    def _na_try_send(self, i, T):
+        k = self.Iter[i]
+        if self.sent[i] or not all(self.ack_rcv[(i, j)] >= k - 1 for j in self.out_nbrs[i]):
+            return
+        self.sent[i] = True
+        self._send(i, k, T)
+
+    def _na_try_consume(self, i, T):
+        k = self.Iter[i]
+        if self.consumed[i] or not all(k in self.queue[(j, i)] for j in self.in_nbrs[i]):
+            return
+        for j in self.in_nbrs[i]:
+            self.queue[(j, i)].remove(k)
+            heapq.heappush(self.events, (T + LAT, EV_ACK, j, i, k))       # ACK after the Reduce, to every sender
+        self.consumed[i] = True
+        if self.trace is not None:
+            self.trace.append(("recv", i, k, tuple((j, k) for j in self.in_nbrs[i])))
+
+    def _na_try_complete(self, i, T):
+        k = self.Iter[i]
+        if not (self.computed[i] and self.sent[i] and self.consumed[i]):
+            return
+        D = self.D
+        self._emit(STEP, i, k, k, k % D, [(j, k) for j in self.in_nbrs[i]], (k + 1) % D, T)
+        self.written[i] = k + 1
+        self._na_enter(i, k + 1, T)
+
+    def _na_enter(self, i, k, T):
+        self.Iter[i] = k
+        if self.trace is not None:
+            self.trace.append(("enter", i, k))
+        if k >= self.K:
+            self.state[i] = FINISHED
+            self.finish_time[i] = T
+            return
+        self.computed[i] = self.sent[i] = self.consumed[i] = False
+        self.state[i] = COMPUTING
+        dur = rng.duration_ticks(self.seed, self.delay_kind, self.N, self.mult[i], i, k, self.table)
+        if dur < rng.TICKS_NEVER:
+            heapq.heappush(self.events, (T + dur, EV_DONE, i, 0, k))
+        self._na_try_send(i, T)
+        self._na_try_consume(i, T)
+
+    def _na_check(self):
+        It = self.Iter
+        for i in range(self.N):
+            for j in self.in_nbrs[i]:
+                assert len(self.queue[(j, i)]) <= 1, "a sender has two unconsumed updates at one receiver"
+            for j in range(self.N):
+                if i != j:
+                    assert It[i] - It[j] <= min(self.dist[j][i], 2 * self.dist[i][j]), "NOTIFY-ACK gap bound broken"
+        self.max_gap = max(self.max_gap, max(It) - min(It))
+
+    def _run_notify_ack(self):
+        N = self.N
+        self.ack_rcv = {(j, i): -1 for i in range(N) for j in self.in_nbrs[i]}     # newest ACK j holds from i
+        self.computed, self.sent, self.consumed = [False] * N, [False] * N, [False] * N
+        for i in range(N):
+            self._na_enter(i, 0, 0)
+        if self.check:
+            self._na_check()
+        while self.events:
+            T, kind, a, snd, tag = heapq.heappop(self.events)
+            if self.state[a] != FINISHED or kind == EV_ACK:
+                if kind == EV_ARRIVE:
+                    self.queue[(snd, a)].append(tag)
+                    self.max_queue = max(self.max_queue, len(self.queue[(snd, a)]))
+                    if self.trace is not None:
+                        self.trace.append(("deliver", snd, a, tag))
+                    self._na_try_consume(a, T)
+                elif kind == EV_DONE:
+                    assert self.Iter[a] == tag
+                    self.computed[a] = True
+                else:                            # ACK of receiver `snd` for a's update `tag`
+                    self.ack_rcv[(a, snd)] = max(self.ack_rcv[(a, snd)], tag)
+                    if self.state[a] != FINISHED:
+                        self._na_try_send(a, T)
+                if self.state[a] != FINISHED:
+                    self._na_try_complete(a, T)
+            if self.check:
+                self._na_check()
         self.stalled = any(st != FINISHED for st in self.state)
         return self.records

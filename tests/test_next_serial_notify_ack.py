@@ -1,0 +1,222 @@
+"""Pins for the two comparison options of Sections 3.2 and 3.3 in the oracle: the serial approach
+(Compute, Apply, Send, then Recv and Reduce) and NOTIFY-ACK.  No GPU."""
+import numpy as np
+import pytest
+
+from oracle import arith, protocol, rng
+from paper_1902_01064_amd import inputs
+
+NEVER = float(1 << 62)
+GRAPHS = [("ring6", inputs.ring(6)), ("torus3x3", inputs.torus(3, 3)),
+          ("directed5", inputs.directed_cycle([0, 3, 1, 4, 2])), ("chords12", inputs.ring_with_chords(12, 1, 2))]
+
+
+def weights_for(nb):
+    sym = all(i in nb[j] for i in range(len(nb)) for j in nb[i])
+    return inputs.metropolis_weights(nb) if sym else inputs.uniform_weights(nb)
+
+
+def linear_gradient(N, d, seed):
+    """A gradient that depends on the worker, the iteration AND the parameters it is taken at."""
+    A = np.random.default_rng(seed).normal(size=(N, d, d)) * 0.3
+    return lambda i, k, w: A[i] @ np.asarray(w, np.float64) + 0.1 * k
+
+
+@pytest.mark.parametrize("name,nb", GRAPHS, ids=[g[0] for g in GRAPHS])
+def test_serial_equals_its_closed_form_under_any_delays(name, nb):
+    """Section 3.2, serial approach: gradients are generated with and applied to the same parameters, then the
+    results are averaged: X_{k+1} = W^T (X_k - eta G(X_k)), whatever the compute delays."""
+    N, d, K, eta = len(nb), 9, 7, 0.05
+    W = weights_for(nb)
+    X0 = np.random.default_rng(1).normal(size=(N, d)).astype(np.float32)
+    grad = linear_gradient(N, d, 2)
+    X = X0.astype(np.float64)
+    for k in range(K):
+        X = W.astype(np.float64).T @ (X - eta * np.stack([grad(i, k, X[i]) for i in range(N)]))
+    para = X0.astype(np.float64)
+    for k in range(K):                                    # the parallel approach is a different recurrence
+        para = W.astype(np.float64).T @ para - eta * np.stack([grad(i, k, para[i]) for i in range(N)])
+    assert np.max(np.abs(para - X)) > 1e-3
+    for seed, kind in [(3, rng.DELAY_EXP1), (4, rng.DELAY_BERNOULLI6), (5, rng.DELAY_NONE)]:
+        h = protocol.Hop(nb, W, s=0, b=0, K=K, seed=seed, delay_kind=kind, mult=[1.0 + (i % 3) for i in range(N)],
+                         serial=True, check=True)
+        recs = h.run()
+        assert not h.stalled and h.slots == h.D + 1
+        rings = arith.init_rings(X0, N, h.slots, serial=True)
+        ver = arith.execute(recs, rings, grad, eta)
+        assert ver == [K] * N
+        got = arith.final_params(rings, ver, serial=True).astype(np.float64)
+        assert np.max(np.abs(got - X)) <= 2e-6 * np.max(np.abs(X))
+        # two records per iteration; a REDUCE takes exactly the same-iteration vector of every in-neighbour,
+        # and that vector was produced by an APPLY record earlier in the sequence
+        applied = set()
+        for r in recs:
+            if r.kind == protocol.APPLY:
+                assert r.src_worker == [r.worker] and r.src_slot == [h.D] and r.out_slot == r.k % h.D
+                assert list(r.w32) == [1.0]
+                applied.add((r.worker, r.k))
+            else:
+                assert r.kind == protocol.REDUCE and r.out_slot == h.D
+                assert list(zip(r.src_worker, r.src_tag)) == [(r.worker, r.k)] + [(j, r.k) for j in sorted(nb[r.worker])]
+                assert all((j, t) in applied for j, t in zip(r.src_worker, r.src_tag))
+        assert len(recs) == 2 * N * K
+
+
+def test_serial_sends_after_compute():
+    """Parallel approach: x_k leaves when iteration k is entered.  Serial approach: y_k leaves when Compute and
+    Apply are done.  With unit compute times the first update arrives one tick after time 0 / after time 1 unit."""
+    nb = inputs.ring(4)
+    W = inputs.uniform_weights(nb)
+    first = {}
+    for serial in (False, True):
+        h = protocol.Hop(nb, W, s=0, b=0, K=3, serial=serial, check=True, trace=True)
+        recs = h.run()
+        first[serial] = min(r.time for r in recs if r.kind in (protocol.STEP, protocol.REDUCE))
+    assert first[False] == rng.TICKS_PER_UNIT            # updates were there long before Compute ended
+    assert first[True] == rng.TICKS_PER_UNIT + 1         # Reduce has to wait for what was sent after Compute
+
+
+def test_serial_with_the_queue_options_keeps_every_invariant():
+    """Tokens, backup workers, staleness and skipping are queue rules and do not care which vector is sent:
+    the oracle's own checks (token identity, Theorem 2, gap table) run after every event; identical replicas
+    with a zero gradient stay put, jumps included."""
+    import random
+    rnd = random.Random(7)
+    jumps = 0
+    for case in range(40):
+        name, nb = rnd.choice(GRAPHS)
+        N = len(nb)
+        s = rnd.choice([0, 1, 3])
+        b = rnd.randrange(0, min(len(l) for l in nb))
+        h = protocol.Hop(nb, weights_for(nb), s=s, b=b, K=rnd.choice([5, 12]), max_ig=rnd.choice([0, 2, 5]),
+                         skip_on=rnd.random() < 0.6, max_skip=rnd.choice([2, 10]), trigger=rnd.choice([0, 1]),
+                         seed=100 + case, delay_kind=rnd.choice([0, 1, 2]),
+                         mult=[rnd.choice([1.0, 1.0, 4.0]) for _ in nb], serial=True, check=True)
+        recs = h.run()
+        assert not h.stalled
+        jumps += h.n_jumps
+        p0 = np.random.default_rng(case).normal(size=5).astype(np.float32)
+        rings = arith.init_rings(p0, N, h.slots, serial=True)
+        ver = arith.execute(recs, rings, arith.GradZero(), 0.1)
+        assert ver == [h.K] * N
+        got = arith.final_params(rings, ver, serial=True)
+        assert np.max(np.abs(got - p0)) <= 4e-7 * np.max(np.abs(p0)) * h.K
+        for r in recs:
+            if r.kind == protocol.JUMP:
+                assert r.src_slot[0] == h.D and r.out_slot == h.D        # x_cur renewed in place
+    assert jumps > 10
+
+
+def iterations_from_trace(trace, N):
+    it, states = [0] * N, []
+    for item in trace:
+        if item[0] == "enter":
+            it[item[1]] = item[2]
+            states.append(tuple(it))
+    return states
+
+
+def scipy_distances(nb):
+    from scipy.sparse import csr_matrix
+    from scipy.sparse.csgraph import shortest_path
+    N = len(nb)
+    adj = np.zeros((N, N))
+    for i, lst in enumerate(nb):
+        for j in lst:
+            adj[j, i] = 1                                  # edge j -> i: j sends to i
+    return shortest_path(csr_matrix(adj), method="D", unweighted=True)
+
+
+@pytest.mark.parametrize("name,nb", GRAPHS, ids=[g[0] for g in GRAPHS])
+def test_notify_ack_gap_row_of_the_table(name, nb):
+    """Gap table, row "Using NOTIFY-ACK": Iter(i) - Iter(j) <= 1 for j in N_in(i), <= 2 for i in N_in(j),
+    <= min(len(j -> i), 2 len(i -> j)) for any pair.  Judged outside the oracle (iterations rebuilt from the
+    trace, path lengths from scipy), over random delays and with each worker frozen in turn."""
+    N = len(nb)
+    W = weights_for(nb)
+    dist = scipy_distances(nb)
+    worst = np.zeros((N, N))
+    runs = [dict(seed=s, delay_kind=rng.DELAY_EXP1, mult=[1.0 + 2.0 * ((i + s) % 3 == 0) for i in range(N)]) for s in range(4)]
+    runs += [dict(seed=9, delay_kind=rng.DELAY_EXP1, mult=[NEVER if i == f else 1.0 for i in range(N)]) for f in range(N)]
+    for kw in runs:
+        h = protocol.Hop(nb, W, s=0, b=0, K=30, notify_ack=True, check=True, trace=True, **kw)
+        h.run()
+        assert h.stalled == any(m >= NEVER for m in kw["mult"])
+        for st in iterations_from_trace(h.trace, N):
+            a = np.array(st, dtype=float)
+            worst = np.maximum(worst, a[:, None] - a[None, :])         # worst[i][j] = max Iter(i) - Iter(j)
+    for i in range(N):
+        for j in range(N):
+            if i != j:
+                assert worst[i, j] <= min(dist[j, i], 2 * dist[i, j])
+                if j in nb[i]:
+                    assert worst[i, j] <= 1                            # a receiver is at most 1 ahead of its sender
+                if i in nb[j]:
+                    assert worst[i, j] <= 2                            # a sender at most 2 ahead of its receiver
+    # the adjacent bounds are attained: a receiver gets 1 ahead of a sender; a sender gets 2 ahead of a receiver
+    # that does not send back to it (where both send to each other, the 1 of the other direction binds)
+    assert max(worst[i, j] for i in range(N) for j in nb[i]) == 1
+    one_way = [worst[i, j] for j in range(N) for i in nb[j] if j not in nb[i]]
+    assert (max(one_way) == 2) if one_way else name != "directed5"
+
+
+def test_notify_ack_attains_the_pair_bound_and_token_queues_cover_it():
+    """With a frozen worker f everyone else runs until something stops it.  Token queues with max_ig = 2 have the
+    same bound for every pair (Theorem 2) and reach it exactly; NOTIFY-ACK reaches it on the directed cycle and
+    the torus and never exceeds what the token queues reach: the token queue is the more general rule that
+    covers it (Section 1: NOTIFY-ACK is a special case of the queue-based approach)."""
+    for name, nb in GRAPHS:
+        N = len(nb)
+        W = weights_for(nb)
+        dist = scipy_distances(nb)
+        for f in range(N):
+            mult = [NEVER if i == f else 1.0 for i in range(N)]
+            final = {}
+            for mode, kw in (("notify_ack", dict(notify_ack=True)), ("tokens", dict(max_ig=2))):
+                h = protocol.Hop(nb, W, s=0, b=0, K=40, seed=1, delay_kind=rng.DELAY_EXP1, mult=mult, check=True, **kw)
+                h.run()
+                final[mode] = list(h.Iter)
+            bound = [int(min(dist[f, i], 2 * dist[i, f])) for i in range(N)]
+            assert final["tokens"] == bound
+            assert all(a <= t for a, t in zip(final["notify_ack"], final["tokens"]))
+            if name in ("torus3x3", "directed5"):
+                assert final["notify_ack"] == bound
+
+
+def test_notify_ack_is_standard_training():
+    """The protocol only moves records in time: every (worker, iteration) averages exactly its in-neighbours'
+    vectors of the same iteration with the weights of W, and the parameters follow X_{k+1} = W^T X_k - eta G_k;
+    at no time does a receiver hold two unconsumed updates of one sender (checked by the oracle at every event)."""
+    for name, nb in GRAPHS:
+        N, d, K, eta = len(nb), 6, 8, 0.05
+        W = weights_for(nb)
+        X0 = np.random.default_rng(3).normal(size=(N, d)).astype(np.float32)
+        grad = linear_gradient(N, d, 4)
+        h = protocol.Hop(nb, W, s=0, b=0, K=K, seed=11, delay_kind=rng.DELAY_EXP1, mult=[1.0 + (i % 2) for i in range(N)],
+                         notify_ack=True, check=True)
+        recs = h.run()
+        assert not h.stalled and len(recs) == N * K and h.D == 4 and h.max_queue == 1
+        for r in recs:
+            assert r.kind == protocol.STEP
+            assert list(zip(r.src_worker, r.src_tag)) == [(r.worker, r.k)] + [(j, r.k) for j in sorted(nb[r.worker])]
+            want = np.array([W[j][r.worker] for j in r.src_worker], dtype=np.float64)
+            assert np.allclose(r.w64, want / want.sum(), rtol=0, atol=1e-15)
+        rings = arith.init_rings(X0, N, h.slots)
+        ver = arith.execute(recs, rings, grad, eta)
+        X = X0.astype(np.float64)
+        for k in range(K):
+            X = W.astype(np.float64).T @ X - eta * np.stack([grad(i, k, X[i]) for i in range(N)])
+        assert np.max(np.abs(arith.final_params(rings, ver) - X)) <= 2e-6 * np.max(np.abs(X))
+        # lock-step (no delays): the same records at the same times as the token-queue protocol
+        a = protocol.Hop(nb, W, s=0, b=0, K=5, notify_ack=True).run()
+        b = protocol.Hop(nb, W, s=0, b=0, K=5, max_ig=2).run()
+        assert [(r.key(), r.time) for r in a] == [(r.key(), r.time) for r in b]
+
+
+def test_notify_ack_refuses_what_it_cannot_support():
+    """Section 3.3: NOTIFY-ACK cannot support backup workers or bounded staleness."""
+    nb = inputs.ring(4)
+    W = inputs.uniform_weights(nb)
+    for kw in (dict(s=1, b=0), dict(s=0, b=1), dict(s=0, b=0, skip_on=True), dict(s=0, b=0, serial=True)):
+        with pytest.raises(protocol.ProtocolError):
+            protocol.Hop(nb, W, K=3, notify_ack=True, **kw)
