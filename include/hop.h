@@ -75,7 +75,11 @@ enum {
     HOP_GRAD_EXTERNAL = 4         /* caller's device buffer, N x d floats, read at every STEP */
 };
 
-enum { HOP_STEP = 0, HOP_JUMP = 1 };
+/* Kinds of schedule records.  STEP: Reduce + Apply of one iteration (parallel approach, Section 3.2).  JUMP: the
+ * Reduce without gradient of a skipped stretch (Section 5).  With the serial approach an iteration is two records:
+ * APPLY (y_k = x_k - eta g(x_k), into the ring slot that is sent) and REDUCE (x_{k+1} = sum_a w'_a y_a, into the
+ * worker's current parameters). */
+enum { HOP_STEP = 0, HOP_JUMP = 1, HOP_APPLY = 2, HOP_REDUCE = 3 };
 
 /* Loss of the linear SVM: hinge, or the log loss the paper's own runs use (Section 7.2). */
 enum { HOP_LOSS_HINGE = 0, HOP_LOSS_LOG = 1 };
@@ -115,6 +119,13 @@ typedef struct {
     uint32_t max_latency;         /* ticks; 0 or 1: every update arrives one tick after its Send, in order;
                                      larger: seeded uniform 1..max_latency per update, so updates on an edge
                                      can overtake each other (Section 6.1) and the ring gets s + max_ig + 2 slots */
+    int32_t serial;               /* 1: the serial approach of Section 3.2 (Compute and Apply on x_k, Send the
+                                     result, then Recv and Reduce) instead of the parallel one; every worker then
+                                     has one more slot, index D, for its current parameters */
+    int32_t notify_ack;           /* 1: NOTIFY-ACK (Section 3.3) instead of token queues: Send(k) waits until every
+                                     out-going neighbour has acknowledged update k - 1, sent right after its Reduce;
+                                     standard training only (s = 0, b = 0, no skipping, not serial, latency 1),
+                                     anything else is HOP_ERR_INVALID_ARG; ring as for max_ig = 2 */
 } hop_opts;
 
 typedef struct {
@@ -129,7 +140,7 @@ typedef struct {
  * ascending id) and writes ring slot out_slot[e] of worker[e]. */
 typedef struct {
     int32_t n_records, n_sources, n_waves, n_workers;
-    int32_t depth;                /* D */
+    int32_t depth;                /* slots per worker (hop_layout) */
     int32_t batch;                /* row ids per STEP record, 0 if none */
     int32_t stalled;              /* 1 if the run ended in HOP_ERR_DEADLOCK */
     int32_t n_jumps;
@@ -137,7 +148,7 @@ typedef struct {
     int32_t reserved;
     const int32_t* kind;          /* HOP_STEP / HOP_JUMP */
     const int32_t* worker;
-    const int32_t* iter;          /* STEP: the iteration k reduced; JUMP: the iteration jumped to */
+    const int32_t* iter;          /* STEP, APPLY, REDUCE: the iteration k; JUMP: the iteration jumped to */
     const uint64_t* time;         /* simulated tick of the Reduce */
     const int32_t* wave;          /* level in the slot-dependence order, see hop_step */
     const int32_t* out_slot;
@@ -171,12 +182,13 @@ const char* hop_strerror(int code);
 int hop_version(void);
 
 /* Fills *o with the defaults (max_ig 0, skip off, max_skip 10, trigger 1, lr 0.01, lambda 1e-4,
- * batch 0, hinge loss, seed 0, momentum 0). */
+ * batch 0, hinge loss, seed 0, momentum 0, latency 1, parallel approach, token queues). */
 int hop_opts_default(hop_opts* o);
 
-/* Ring depth D and slot stride (in floats) used for N workers of d parameters under staleness bound
- * s: D = max_ig + 1 for s >= 1 (Section 6.1's #queues; s + max_ig + 2 when max_latency > 1),
- * max_ig + 2 for s = 0. */
+/* Slots per worker and slot stride (in floats) for d parameters under staleness bound s.  The ring has
+ * D = max_ig + 1 versions for s >= 1 (Section 6.1's #queues; s + max_ig + 2 when max_latency > 1),
+ * max_ig + 2 for s = 0; version v lives in slot v mod D.  depth = D, or D + 1 with the serial approach
+ * (slot D: the worker's current parameters, never sent). */
 int hop_layout(int64_t d, int32_t s, const hop_opts* o, int32_t* depth, int64_t* stride);
 
 /* Bytes of device memory hop_init needs for rings, gradient buffers and scratch. */

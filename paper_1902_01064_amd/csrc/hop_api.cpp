@@ -22,6 +22,7 @@ constexpr int64_t kDenseInPlaceBytes = 2 << 20;
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
 int effective_max_ig(int s, const hop_opts* o) {
+    if (o && o->notify_ack) return 2;      // a sender is never more than 2 iterations ahead of a receiver
     int ig = o ? o->max_ig : 0;
     return ig > 0 ? ig : std::max(s, 1);
 }
@@ -144,7 +145,7 @@ int pack_pairs(const HopMixJob* jobs, int n, std::vector<HopPairJob>& out) {
 }
 
 float* slot_ptr(const hop_ctx* c, int worker, int slot) {
-    return c->ring + ((int64_t)worker * c->D + slot) * c->stride;
+    return c->ring + ((int64_t)worker * c->slots + slot) * c->stride;
 }
 
 // Translate the schedule into device descriptors for the context's current gradient source.
@@ -197,7 +198,7 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                 mj.src[a] = slot_ptr(c, s->src_worker[q], s->src_slot[q]);
                 mj.w[a] = s->src_weight[q];
             }
-            const bool step = s->kind[e] == HOP_STEP;
+            const bool step = s->kind[e] == HOP_STEP || s->kind[e] == HOP_APPLY;     // records that apply a gradient
             if (step && mode != HOP_GRAD_ZERO) {
                 HopGradJob gj;
                 std::memset(&gj, 0, sizeof(gj));
@@ -376,13 +377,15 @@ int hop_opts_default(hop_opts* o) {
     o->seed = 0;
     o->momentum = 0.f;
     o->max_latency = 0;
+    o->serial = 0;
+    o->notify_ack = 0;
     return HOP_OK;
 }
 
 int hop_layout(int64_t d, int32_t s, const hop_opts* o, int32_t* depth, int64_t* stride) {
     if (d < 1 || s < 0) return HOP_ERR_INVALID_ARG;
     int ig = effective_max_ig(s, o);
-    if (depth) *depth = ring_depth(s, ig, o ? o->max_latency : 0);
+    if (depth) *depth = ring_depth(s, ig, o ? o->max_latency : 0) + ((o && o->serial) ? 1 : 0);
     if (stride) *stride = slot_stride(d);
     return HOP_OK;
 }
@@ -422,12 +425,15 @@ static int init_ctx(hop_ctx** out, const hop_graph* g, const float* W, int32_t N
     if (o.max_ig < 0 || o.max_skip < 1 || o.trigger < 0 || o.batch < 0 || o.batch > kMaxBatch ||
         (o.loss != HOP_LOSS_HINGE && o.loss != HOP_LOSS_LOG) || !(o.momentum >= 0.f && o.momentum < 1.f))
         return HOP_ERR_INVALID_ARG;
+    // NOTIFY-ACK supports neither backup workers nor staleness (Section 3.3); it is built for standard training
+    if (o.notify_ack && (s != 0 || b != 0 || o.skip_on || o.serial || o.max_latency > 1)) return HOP_ERR_INVALID_ARG;
     std::unique_ptr<hop_ctx> holder(new (std::nothrow) hop_ctx());
     hop_ctx* c = holder.get();
     if (!c) return HOP_ERR_NOMEM;
     c->N = N; c->d = d; c->s = s; c->b = b; c->opts = o;
     c->max_ig = effective_max_ig(s, &o);
     c->D = ring_depth(s, c->max_ig, o.max_latency);
+    c->slots = c->D + (o.serial ? 1 : 0);
     c->stride = slot_stride(d);
     int rc = HOP_OK;
     c->in_nbrs.assign(N, {});
@@ -472,7 +478,7 @@ static int init_ctx(hop_ctx** out, const hop_graph* g, const float* W, int32_t N
             c->arena_bytes = dev->arena_bytes;
             c->stream = dev->hip_stream;
             c->ring = (float*)dev->arena;
-            c->gbuf = c->ring + (int64_t)N * c->D * c->stride;
+            c->gbuf = c->ring + (int64_t)N * c->slots * c->stride;
             c->partial = c->gbuf + (int64_t)N * c->stride;
             c->vel = o.momentum > 0.f ? c->partial + (int64_t)N * partial_floats(d, o.batch) : nullptr;
         }
@@ -499,7 +505,8 @@ int hop_set_params(hop_ctx* c, const float* p0, int per_worker, int on_device) {
     hipStream_t st = (hipStream_t)c->stream;
     for (int i = 0; i < c->N; ++i) {
         const float* src = per_worker ? p0 + (int64_t)i * c->d : p0;
-        HOP_HIP(c, hipMemcpyAsync(slot_ptr(c, i, 0), src, (size_t)c->d * sizeof(float),
+        // x_0: ring slot 0, or the current-parameter slot of the serial approach
+        HOP_HIP(c, hipMemcpyAsync(slot_ptr(c, i, c->opts.serial ? c->D : 0), src, (size_t)c->d * sizeof(float),
                                   on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, st));
     }
     if (c->vel) HOP_HIP(c, hipMemsetAsync(c->vel, 0, (size_t)c->N * c->stride * sizeof(float), st));
@@ -787,7 +794,9 @@ int hop_step(hop_ctx* c, const hop_schedule* sched, int32_t wave_begin, int32_t 
     }
     for (int p = s->wave_begin[wave_begin]; p < s->wave_begin[wave_end]; ++p) {
         int e = s->wave_order[p];
-        c->version[s->worker[e]] = s->kind[e] == HOP_STEP ? s->iter[e] + 1 : s->iter[e];
+        const int kind = s->kind[e];
+        if (kind == HOP_STEP || kind == HOP_REDUCE) c->version[s->worker[e]] = s->iter[e] + 1;
+        else if (kind == HOP_JUMP) c->version[s->worker[e]] = s->iter[e];
     }
     c->next_wave = wave_end;
     return HOP_OK;
@@ -803,13 +812,13 @@ int hop_use_graph(hop_ctx* c, int enable) {
 int hop_params(hop_ctx* c, int32_t worker, const float** dev_ptr, int32_t* iter) {
     if (!c || worker < 0 || worker >= c->N) return HOP_ERR_INVALID_ARG;
     if (!c->has_device) return HOP_ERR_NO_DEVICE;
-    if (dev_ptr) *dev_ptr = slot_ptr(c, worker, c->version[worker] % c->D);
+    if (dev_ptr) *dev_ptr = slot_ptr(c, worker, c->opts.serial ? c->D : c->version[worker] % c->D);
     if (iter) *iter = c->version[worker];
     return HOP_OK;
 }
 
 int hop_slot(hop_ctx* c, int32_t worker, int32_t slot, float** dev_ptr) {
-    if (!c || !dev_ptr || worker < 0 || worker >= c->N || slot < 0 || slot >= c->D) return HOP_ERR_INVALID_ARG;
+    if (!c || !dev_ptr || worker < 0 || worker >= c->N || slot < 0 || slot >= c->slots) return HOP_ERR_INVALID_ARG;
     if (!c->has_device) return HOP_ERR_NO_DEVICE;
     *dev_ptr = slot_ptr(c, worker, slot);
     return HOP_OK;

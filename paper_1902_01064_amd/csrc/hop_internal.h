@@ -90,7 +90,7 @@ float synth_scale(float variance);
 
 // ---- schedule ----------------------------------------------------------------------
 struct hop_schedule {
-    int N = 0, D = 0, K = 0, batch = 0, stalled = 0, n_jumps = 0, n_waves = 0, late_sends = 0;
+    int N = 0, D = 0, K = 0, batch = 0, stalled = 0, n_jumps = 0, n_waves = 0, late_sends = 0;   // D: slots per worker in memory
     std::vector<int32_t> kind, worker, iter, wave, out_slot, src_begin, src_worker, src_tag, src_slot;
     std::vector<uint64_t> time;
     std::vector<float> src_weight;
@@ -142,6 +142,7 @@ struct HopProfile {
 
 struct hop_ctx {
     int N = 0, s = 0, b = 0, D = 0, max_ig = 0;
+    int slots = 0;                      // slots per worker in memory: D, plus the current-parameter slot D when serial
     int64_t d = 0, stride = 0;
     hop_opts opts{};
     std::vector<std::vector<int>> in_nbrs, out_nbrs;

@@ -7,6 +7,12 @@
 // iterations), Section 6.1 (one queue per iteration: version v lives in ring slot v mod D) and
 // Section 6.2 (a) (stale updates dropped at dequeue).
 //
+// Options beside the paper's own design: the serial approach of Section 3.2 (Compute and Apply on x_k, Send
+// the result, then Recv and Reduce: two records per iteration, the current parameters in slot D of every
+// worker) and NOTIFY-ACK of Section 3.3 (no token queues: Send(k) waits for every out-going neighbour's
+// acknowledgement of update k - 1, which leaves right after the Reduce that consumed it; Recv and Reduce run
+// beside Compute; standard training only).
+//
 // Time is integer ticks (2^20 per time unit); an update sent at T is visible at T + 1; Reduce,
 // Apply, token moves and jumps take no time; simultaneous events run in the order
 // (time, arrival before compute-done, worker, sender, tag).  All randomness is a pure function of
@@ -56,7 +62,7 @@ namespace {
 constexpr uint64_t TICKS_PER_UNIT = 1ull << 20;
 constexpr uint64_t LAT = 1;
 
-enum { EV_ARRIVE = 0, EV_DONE = 1 };
+enum { EV_ARRIVE = 0, EV_DONE = 1, EV_ACK = 2 };
 enum { COMPUTING = 0, WAIT_RECV = 1, WAIT_TOKEN = 2, FINISHED = 3 };
 
 struct Event {
@@ -76,6 +82,7 @@ struct Sim {
     const hop_delay_model* dm;
     hop_schedule* out;
     int N, s, b, K, D, max_ig;
+    bool serial = false;
     std::vector<int> in_ptr;                    // in-edge e = in_ptr[i] + position of j in N_in(i)
     std::vector<std::vector<int>> take_edge;    // per worker r: in-edge ids (r -> j), j in N_out(r)
     std::vector<std::vector<int>> queue;        // per in-edge: tags waiting in UpdateQ
@@ -188,7 +195,7 @@ struct Sim {
             int64_t rows = c->data[i].rows;
             for (int m = 0; m < out->batch; ++m) {
                 int32_t r_m = 0;
-                if (kind == HOP_STEP && rows > 0)
+                if ((kind == HOP_STEP || kind == HOP_APPLY) && rows > 0)
                     r_m = (int32_t)(hoprng::mix(c->opts.seed, hoprng::STREAM_BATCH, (uint64_t)i,
                                                 (uint64_t)k_label, (uint64_t)m) % (uint64_t)rows);
                 out->batch_rows.push_back(r_m);
@@ -202,6 +209,13 @@ struct Sim {
         return true;
     }
 
+    void send(int i, int k, uint64_t T) {
+        for (int j : c->out_nbrs[i]) {
+            events.push(Event{T + latency(i, j, k), EV_ARRIVE, j, i, k});
+            if (iter[j] > k) out->late_sends += 1;         // Section 6.2 (b): the receiver is already past it
+        }
+    }
+
     void enter(int i, int k, uint64_t T) {
         iter[i] = k;
         const auto& nb = c->in_nbrs[i];
@@ -211,10 +225,7 @@ struct Sim {
             state[i] = FINISHED;
             out->finish_time[i] = T;
         } else {
-            for (int j : c->out_nbrs[i]) {
-                events.push(Event{T + latency(i, j, k), EV_ARRIVE, j, i, k});
-                if (iter[j] > k) out->late_sends += 1;     // Section 6.2 (b): the receiver is already past it
-            }
+            if (!serial) send(i, k, T);                    // parallel approach: x_k leaves on entering iteration k
             uint64_t dur = duration(i, k);
             if (dur < HOP_TICKS_NEVER) events.push(Event{T + dur, EV_DONE, i, 0, k});
             state[i] = COMPUTING;
@@ -234,8 +245,13 @@ struct Sim {
         std::vector<std::pair<int, int>> acc;
         if (!recv_eval(i, k0, acc)) return;
         recv_commit(i, k0);
-        emit(HOP_STEP, i, k0, k0, k0 % D, acc, (k0 + 1) % D, T);
-        written[i] = k0 + 1;
+        if (serial) {
+            // the sent vectors (the worker's own y_k sits in ring slot k mod D) reduce into its current parameters
+            emit(HOP_REDUCE, i, k0, k0, k0 % D, acc, D, T);
+        } else {
+            emit(HOP_STEP, i, k0, k0, k0 % D, acc, (k0 + 1) % D, T);
+            written[i] = k0 + 1;
+        }
         if (c->opts.skip_on && !c->out_nbrs[i].empty()) {
             int slowest = iter[c->out_nbrs[i][0]];
             for (int j : c->out_nbrs[i]) slowest = std::min(slowest, iter[j]);
@@ -246,8 +262,12 @@ struct Sim {
                     int kp = k0 + J;
                     if (recv_eval(i, kp - 1, acc)) {
                         recv_commit(i, kp - 1);
-                        emit(HOP_JUMP, i, kp - 1, kp, (k0 + 1) % D, acc, kp % D, T);
-                        written[i] = kp;
+                        if (serial) {
+                            emit(HOP_JUMP, i, kp - 1, kp, D, acc, D, T);     // current parameters renewed in place
+                        } else {
+                            emit(HOP_JUMP, i, kp - 1, kp, (k0 + 1) % D, acc, kp % D, T);
+                            written[i] = kp;
+                        }
                         for (int e : take_edge[i]) token[e] -= J;
                         const auto& nb = c->in_nbrs[i];
                         for (size_t p = 0; p < nb.size(); ++p) token[in_ptr[i] + (int)p] += J - 1;
@@ -262,8 +282,95 @@ struct Sim {
         try_advance(i, T);
     }
 
+    // ---- NOTIFY-ACK: per worker, what the current iteration still needs before it may advance (Section 3.3's
+    // Assumption: computed, sent, received) and the newest acknowledgement held per out-going edge
+    std::vector<char> computed, sent, consumed;
+    std::vector<int> ack_rcv;                   // per in-edge (sender -> receiver): newest tag the receiver acknowledged
+
+    void na_try_send(int i, uint64_t T) {
+        if (sent[i]) return;
+        for (int e : take_edge[i])
+            if (ack_rcv[e] < iter[i] - 1) return;
+        sent[i] = 1;
+        send(i, iter[i], T);
+    }
+
+    void na_try_consume(int i, uint64_t T) {
+        if (consumed[i]) return;
+        const int k = iter[i];
+        const auto& nb = c->in_nbrs[i];
+        for (size_t p = 0; p < nb.size(); ++p) {
+            const auto& q = queue[in_ptr[i] + (int)p];
+            if (std::find(q.begin(), q.end(), k) == q.end()) return;
+        }
+        for (size_t p = 0; p < nb.size(); ++p) {
+            auto& q = queue[in_ptr[i] + (int)p];
+            q.erase(std::find(q.begin(), q.end(), k));
+            events.push(Event{T + LAT, EV_ACK, nb[p], i, k});      // to every sender, right after the Reduce
+        }
+        consumed[i] = 1;
+    }
+
+    void na_enter(int i, int k, uint64_t T) {
+        iter[i] = k;
+        if (k >= K) {
+            state[i] = FINISHED;
+            out->finish_time[i] = T;
+            return;
+        }
+        computed[i] = sent[i] = consumed[i] = 0;
+        state[i] = COMPUTING;
+        uint64_t dur = duration(i, k);
+        if (dur < HOP_TICKS_NEVER) events.push(Event{T + dur, EV_DONE, i, 0, k});
+        na_try_send(i, T);
+        na_try_consume(i, T);
+    }
+
+    void na_try_complete(int i, uint64_t T) {
+        if (!(computed[i] && sent[i] && consumed[i])) return;
+        const int k = iter[i];
+        std::vector<std::pair<int, int>> acc;
+        for (int j : c->in_nbrs[i]) acc.emplace_back(j, k);
+        emit(HOP_STEP, i, k, k, k % D, acc, (k + 1) % D, T);
+        written[i] = k + 1;
+        na_enter(i, k + 1, T);
+    }
+
+    int run_notify_ack() {
+        computed.assign(N, 0);
+        sent.assign(N, 0);
+        consumed.assign(N, 0);
+        ack_rcv.assign(in_ptr[N], -1);
+        for (int i = 0; i < N; ++i) na_enter(i, 0, 0);
+        while (!events.empty() && err == HOP_OK) {
+            Event ev = events.top();
+            events.pop();
+            const int a = ev.worker;
+            if (ev.kind == EV_ACK) {
+                // `a` is the sender of the update, ev.sender the receiver that consumed it: in-edge (a -> ev.sender)
+                const auto& nb = c->in_nbrs[ev.sender];
+                int p = (int)(std::lower_bound(nb.begin(), nb.end(), a) - nb.begin());
+                int e = in_ptr[ev.sender] + p;
+                ack_rcv[e] = std::max(ack_rcv[e], ev.tag);
+                if (state[a] != FINISHED) na_try_send(a, ev.time);
+            } else if (state[a] == FINISHED) {
+                continue;
+            } else if (ev.kind == EV_ARRIVE) {
+                const auto& nb = c->in_nbrs[a];
+                int p = (int)(std::lower_bound(nb.begin(), nb.end(), ev.sender) - nb.begin());
+                queue[in_ptr[a] + p].push_back(ev.tag);
+                na_try_consume(a, ev.time);
+            } else {
+                computed[a] = 1;
+            }
+            if (state[a] != FINISHED) na_try_complete(a, ev.time);
+        }
+        return finish();
+    }
+
     int run() {
         N = c->N; s = c->s; b = c->b; D = c->D; max_ig = c->max_ig;
+        serial = c->opts.serial != 0;
         in_ptr.assign(N + 1, 0);
         for (int i = 0; i < N; ++i) in_ptr[i + 1] = in_ptr[i] + (int)c->in_nbrs[i].size();
         int E = in_ptr[N];
@@ -282,6 +389,7 @@ struct Sim {
         written.assign(N, 0);
         out->finish_time.assign(N, 0);
         out->src_begin.push_back(0);
+        if (c->opts.notify_ack) return run_notify_ack();
         for (int i = 0; i < N; ++i) enter(i, 0, 0);
         while (!events.empty() && err == HOP_OK) {
             Event ev = events.top();
@@ -292,10 +400,21 @@ struct Sim {
                 queue[in_ptr[ev.worker] + p].push_back(ev.tag);
                 if (state[ev.worker] == WAIT_RECV) try_recv(ev.worker, ev.time);
             } else {
+                if (serial) {
+                    // Apply, then Send: y_k = x_k - eta g(x_k) into the ring slot that the neighbours will read
+                    static const std::vector<std::pair<int, int>> none;
+                    emit(HOP_APPLY, ev.worker, ev.tag, ev.tag, D, none, ev.tag % D, ev.time);
+                    written[ev.worker] = ev.tag;
+                    send(ev.worker, ev.tag, ev.time);
+                }
                 state[ev.worker] = WAIT_RECV;
                 try_recv(ev.worker, ev.time);
             }
         }
+        return finish();
+    }
+
+    int finish() {
         if (err != HOP_OK) return err;
         out->final_iter.assign(iter.begin(), iter.end());
         for (int i = 0; i < N; ++i)
@@ -340,7 +459,7 @@ void build_waves(hop_schedule* sc) {
 
 int hop_run_protocol(const hop_ctx* ctx, const hop_delay_model* dm, int K, hop_schedule* out) {
     out->N = ctx->N;
-    out->D = ctx->D;
+    out->D = ctx->slots;
     out->K = K;
     bool any_rows = false;
     for (const auto& dd : ctx->data) any_rows = any_rows || dd.rows > 0;

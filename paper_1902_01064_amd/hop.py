@@ -16,7 +16,7 @@ HOP_ERR_ARENA_TOO_SMALL, HOP_ERR_DEADLOCK, HOP_ERR_SLOT_DEAD, HOP_ERR_HIP = -5, 
 HOP_ERR_NO_DEVICE, HOP_ERR_STATE, HOP_ERR_NOMEM = -9, -10, -11
 HOP_DELAY_NONE, HOP_DELAY_EXP1, HOP_DELAY_BERNOULLI6, HOP_DELAY_TABLE = 0, 1, 2, 3
 HOP_GRAD_ZERO, HOP_GRAD_SVM_DENSE, HOP_GRAD_SVM_CSR, HOP_GRAD_SYNTH, HOP_GRAD_EXTERNAL = 0, 1, 2, 3, 4
-HOP_STEP, HOP_JUMP = 0, 1
+HOP_STEP, HOP_JUMP, HOP_APPLY, HOP_REDUCE = 0, 1, 2, 3
 HOP_KERNEL_MIX, HOP_KERNEL_GRAD, HOP_KERNEL_SYNTH = 0, 1, 2
 HOP_LOSS_HINGE, HOP_LOSS_LOG = 0, 1
 HOP_TICKS_NEVER = 1 << 62
@@ -52,7 +52,8 @@ class hop_opts(C.Structure):
     _fields_ = [("max_ig", C.c_int32), ("skip_on", C.c_int32), ("max_skip", C.c_int32),
                 ("trigger", C.c_int32), ("lr", C.c_float), ("lambda_", C.c_float),
                 ("batch", C.c_int32), ("loss", C.c_int32), ("seed", C.c_uint64),
-                ("momentum", C.c_float), ("max_latency", C.c_uint32)]
+                ("momentum", C.c_float), ("max_latency", C.c_uint32), ("serial", C.c_int32),
+                ("notify_ack", C.c_int32)]
 
 
 class hop_delay_model(C.Structure):
@@ -159,12 +160,13 @@ def _np_i32(a):
 
 
 def make_opts(max_ig=0, skip_on=False, max_skip=10, trigger=1, lr=0.01, lam=1e-4, batch=0, seed=0,
-              loss=HOP_LOSS_HINGE, momentum=0.0, max_latency=0):
+              loss=HOP_LOSS_HINGE, momentum=0.0, max_latency=0, serial=False, notify_ack=False):
     o = hop_opts()
     _check(load().hop_opts_default(C.byref(o)), "hop_opts_default")
     o.max_ig, o.skip_on, o.max_skip, o.trigger = int(max_ig), int(bool(skip_on)), int(max_skip), int(trigger)
     o.lr, o.lambda_, o.batch, o.seed = float(lr), float(lam), int(batch), int(seed)
     o.loss, o.momentum, o.max_latency = int(loss), float(momentum), int(max_latency)
+    o.serial, o.notify_ack = int(bool(serial)), int(bool(notify_ack))
     return o
 
 

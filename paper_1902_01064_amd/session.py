@@ -16,7 +16,8 @@ class Session:
         self.opts = hop.make_opts(max_ig=c["max_ig"], skip_on=c["skip_on"], max_skip=c["max_skip"],
                                   trigger=c["trigger"], lr=c["lr"], lam=c["lam"], batch=c["batch"],
                                   seed=c["seed"], loss=c.get("loss", 0), momentum=c.get("momentum", 0.0),
-                                  max_latency=c.get("max_latency", 0))
+                                  max_latency=c.get("max_latency", 0), serial=c.get("serial", False),
+                                  notify_ack=c.get("notify_ack", False))
         self.N, self.d = c["N"], c["d"]
         need = hop.hop_arena_bytes(self.N, self.d, c["s"], self.opts)
         self.arena = torch.zeros(need // 4, dtype=torch.float32, device=self.dev)

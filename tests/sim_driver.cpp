@@ -46,7 +46,9 @@ int main() {
             for (int b : {0, 1})
                 for (int skip : {0, 1})
                     for (uint32_t lat : {0u, 1u << 20})
+                      for (int option : {0, 1, 2})                // 0 token queues, 1 serial approach, 2 NOTIFY-ACK
                         for (int kind : {HOP_DELAY_NONE, HOP_DELAY_EXP1, HOP_DELAY_BERNOULLI6}) {
+                            if (option == 2 && (s != 0 || b != 0 || skip || lat > 1)) continue;
                             const auto& nb = graphs[gi];
                             const int N = (int)nb.size();
                             int mindeg = N;
@@ -59,8 +61,11 @@ int main() {
                             c.opts.seed = 17 * gi + s;
                             c.opts.batch = 4;
                             c.opts.max_latency = lat;
-                            c.max_ig = s > 0 ? s : 1;
+                            c.opts.serial = option == 1;
+                            c.opts.notify_ack = option == 2;
+                            c.max_ig = option == 2 ? 2 : (s > 0 ? s : 1);
                             c.D = s >= 1 ? (lat > 1 ? s + c.max_ig + 2 : c.max_ig + 1) : c.max_ig + 2;
+                            c.slots = c.D + (option == 1 ? 1 : 0);
                             c.in_nbrs = nb;
                             c.out_nbrs.assign(N, {});
                             for (int i = 0; i < N; ++i)

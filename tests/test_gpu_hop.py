@@ -24,6 +24,7 @@ pytestmark = pytest.mark.gpu
 STEP_TOL = 1e-5
 RUN_TOL = 1e-4
 LOSS = {0: "hinge", 1: "log"}
+GRADIENT_KINDS = (protocol.STEP, protocol.APPLY)          # records that take and apply a gradient
 
 
 
@@ -31,13 +32,14 @@ def oracle_schedule(c, K):
     h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], K, max_ig=c["max_ig"], skip_on=c["skip_on"],
                      max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
                      delay_kind=c["delay_kind"], mult=c["mult"], check=False,
-                     max_latency=c.get("max_latency", 1))
+                     max_latency=c.get("max_latency", 1), serial=c.get("serial", False),
+                     notify_ack=c.get("notify_ack", False))
     recs = h.run()
     return h, recs
 
 
 def assert_schedule_equal(sched, h, recs):
-    assert sched.n_records == len(recs) and sched.depth == h.D and not sched.stalled
+    assert sched.n_records == len(recs) and sched.depth == h.slots and not sched.stalled
     assert list(sched.kind) == [r.kind for r in recs]
     assert list(sched.worker) == [r.worker for r in recs]
     assert list(sched.iter) == [r.k for r in recs]
@@ -47,7 +49,7 @@ def assert_schedule_equal(sched, h, recs):
     assert list(sched.src_slot) == [t for r in recs for t in r.src_slot]
     w_ref = np.concatenate([r.w32 for r in recs])
     assert np.array_equal(sched.src_weight.view(np.uint32), w_ref.view(np.uint32))
-    assert waves.check_waves(recs, list(sched.wave), h.N, h.D)
+    assert waves.check_waves(recs, list(sched.wave), h.N, h.slots)
 
 
 class FollowKernelAtTies:
@@ -114,7 +116,7 @@ def record_terms(c, data_np, base, rec, vecs, g, vel_before, mu, scale_of):
     mag = sum(abs(float(w)) * np.abs(x.astype(np.float64)) for w, x in zip(rec.w32, vecs))
     n = np.full(vecs[0].shape, float(len(vecs)))
     extra = 0.0
-    if rec.kind != protocol.STEP or g is None:
+    if rec.kind not in GRADIENT_KINDS or g is None:
         return mag, n, extra
     gm, gn = np.abs(np.asarray(g, np.float64)), 1.0
     if c["model"] in ("dense", "csr"):
@@ -164,7 +166,7 @@ def attach(sess, c, p0, data):
 
 def read_active(sess, sched, recs):
     """Which minibatch samples the kernel treated as active, per STEP record (from its coefficients)."""
-    return {(r.worker, r.k): sess.coef(e) != 0 for e, r in enumerate(recs) if r.kind == protocol.STEP}
+    return {(r.worker, r.k): sess.coef(e) != 0 for e, r in enumerate(recs) if r.kind in GRADIENT_KINDS}
 
 
 def run_parity(c, per_wave_check=True, strict=False, strict_run_tol=None):
@@ -189,16 +191,17 @@ def run_parity(c, per_wave_check=True, strict=False, strict_run_tol=None):
         has_hinge = c["model"] in ("dense", "csr") and c.get("loss", 0) == 0
         mu = float(c.get("momentum", 0.0))
         N, d = c["N"], c["d"]
+        serial = bool(c.get("serial", False))
 
         # ---- the run as a whole: both sides from p0, the oracle in sequence order ----
         sess.step()
         sess.sync()
         gpu_active = read_active(sess, sched, recs) if has_hinge else {}
-        rings = arith.init_rings(p0.numpy(), N, h.D)
+        rings = arith.init_rings(p0.numpy(), N, h.slots, serial)
         grad = FollowKernelAtTies(base, gpu_active, scale_of) if has_hinge else base
         vel = np.zeros((N, d), dtype=np.float32) if mu > 0 else None
         ver = arith.execute(recs, rings, grad, c["lr"], vel=vel, mu=mu)
-        want = arith.final_params(rings, ver)
+        want = arith.final_params(rings, ver, serial)
         got, its = sess.params()
         assert its == ver == [c["K"]] * N
         if mu > 0:
@@ -212,7 +215,7 @@ def run_parity(c, per_wave_check=True, strict=False, strict_run_tol=None):
         worst_step = strict_step = worst_excess = 0.0
         if per_wave_check:
             sess.set_params(p0)
-            rings = arith.init_rings(p0.numpy(), N, h.D)
+            rings = arith.init_rings(p0.numpy(), N, h.slots, serial)
             vel = np.zeros((N, d), dtype=np.float32) if mu > 0 else None
             for w in range(sched.n_waves):
                 sess.upload_rings(rings)
@@ -222,14 +225,14 @@ def run_parity(c, per_wave_check=True, strict=False, strict_run_tol=None):
                 sess.sync()
                 members = [int(e) for e in sched.wave_order[sched.wave_begin[w]:sched.wave_begin[w + 1]]]
                 active = {(recs[e].worker, recs[e].k): sess.coef(e) != 0
-                          for e in members if has_hinge and recs[e].kind == protocol.STEP}
+                          for e in members if has_hinge and recs[e].kind in GRADIENT_KINDS}
                 after = sess.ring_snapshot()
                 vel_after = sess.vel_snapshot() if mu > 0 else None
                 grad = KeepGradient(FollowKernelAtTies(base, active, scale_of) if has_hinge else base)
                 for e in members:         # members of a wave touch no slot in a conflicting way
                     r = recs[e]
                     vecs = [rings[j, sl].copy() for j, sl in zip(r.src_worker, r.src_slot)]
-                    vel_before = vel[r.worker].copy() if mu > 0 and r.kind == protocol.STEP else None
+                    vel_before = vel[r.worker].copy() if mu > 0 and r.kind in GRADIENT_KINDS else None
                     grad.last = None
                     ref = arith.apply_record(rings, r, grad, c["lr"], vel, mu)
                     got_vec = after[r.worker, r.out_slot]
@@ -239,7 +242,7 @@ def run_parity(c, per_wave_check=True, strict=False, strict_run_tol=None):
                     worst_excess = max(worst_excess, excess)
                     worst_step = max(worst_step, rel_err(got_vec, ref))
                     strict_step = max(strict_step, strict_rel_err(got_vec, ref))
-                    if mu > 0 and r.kind == protocol.STEP and c["model"] != "none":
+                    if mu > 0 and r.kind in GRADIENT_KINDS and c["model"] != "none":
                         worst_step = max(worst_step, rel_err(vel_after[r.worker], vel[r.worker]))
                 flips += grad.inner.flips if has_hinge else 0
             assert worst_step <= STEP_TOL, worst_step
@@ -513,6 +516,56 @@ def test_out_of_order_delivery(cfgn, over):
     """Updates that overtake each other on an edge (Section 6.1): deeper rings (s + max_ig + 2 slots),
     same parity bars."""
     run_parity(inputs.config(cfgn, **over))
+
+
+@pytest.mark.parametrize("cfgn,over", [
+    (1, dict(serial=True)),
+    (2, dict(d=4096 + 4, rows=256, K=24, serial=True)),
+    (3, dict(d=1 << 13, rows=1024, K=30, serial=True)),
+    (4, dict(d=(1 << 13) + 1, K=40, serial=True)),
+    (4, dict(d=(1 << 13) + 1, K=40, serial=True, momentum=0.9)),
+    (3, dict(d=1 << 13, rows=1024, K=20, serial=True, momentum=0.9, loss=1)),
+])
+def test_serial_approach(cfgn, over):
+    """Section 3.2's serial approach through the whole path: APPLY records (gradient taken at and applied to the
+    current parameters, result into the ring slot that is sent) and REDUCE records (ring slots into the current
+    parameters), with the queue options of the named workloads (staleness, backup workers, jumps that renew the
+    current parameters in place), every gradient source, momentum."""
+    c = inputs.config(cfgn, **over)
+    run_parity(c)
+    if cfgn == 1:                        # config 1 is lock-step: the schedule is the closed form's, two records per update
+        h, recs = oracle_schedule(c, c["K"])
+        assert [r.kind for r in recs].count(protocol.APPLY) == c["N"] * c["K"] == [r.kind for r in recs].count(protocol.REDUCE)
+
+
+@pytest.mark.parametrize("model", ["dense", "synth", "csr"])
+def test_notify_ack(model):
+    """Section 3.3's NOTIFY-ACK instead of token queues (standard training, the only mode it supports): same
+    records as standard training at other times; 9 workers on a torus with Exp(1) delays and a 3x straggler."""
+    nb = inputs.torus(3, 3)
+    mult = [1.0] * 9
+    mult[4] = 3.0
+    c = dict(inputs.config(3 if model == "csr" else 1, d=2052, rows=256, K=14), in_nbrs=nb, W=inputs.metropolis_weights(nb),
+             N=9, s=0, b=0, skip_on=False, mult=mult, delay_kind=hop.HOP_DELAY_EXP1, model=model, grad_var=1e-3,
+             notify_ack=True, name="notify-ack, " + model)
+    if model == "synth":
+        c.update(batch=0, rows=0)
+    elif model == "dense":
+        c.update(batch=32)
+    else:
+        c.update(batch=16, nnz=8)
+    run_parity(c)
+
+
+def test_random_modes_on_the_serial_approach():
+    """16 more seeded random combinations (graphs, staleness, backup workers, tokens, skipping, delays, models,
+    losses, momentum, ragged sizes), all on the serial approach."""
+    import random
+    rnd = random.Random(6)
+    for case in range(16):
+        c = random_mode(rnd, 100 + case)
+        c.update(serial=True, max_latency=1, name="random serial mode %d" % case)
+        run_parity(c)
 
 
 def test_gpu_run_equals_matrix_power_without_the_oracle():

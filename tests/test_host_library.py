@@ -31,11 +31,18 @@ def test_library_exports_every_declared_symbol():
     assert hop.hop_strerror(hop.HOP_ERR_BAD_BACKUP).startswith("backup")
 
 
+def code(fn):
+    with pytest.raises(hop.HopError) as e:
+        fn()
+    return e.value.code
+
+
 def host_ctx(c, **over):
     row_ptr, col = inputs.to_csr(c["in_nbrs"])
     o = hop.make_opts(max_ig=c["max_ig"], skip_on=c["skip_on"], max_skip=c["max_skip"],
                       trigger=c["trigger"], lr=c["lr"], lam=c["lam"], batch=c["batch"], seed=c["seed"],
-                      max_latency=c.get("max_latency", 0))
+                      max_latency=c.get("max_latency", 0), serial=c.get("serial", False),
+                      notify_ack=c.get("notify_ack", False))
     ctx = hop.hop_init(row_ptr, col, c["W"], c["N"], c["d"], c["s"], c["b"], o)
     for i in range(c["N"]):
         if c["batch"]:
@@ -47,12 +54,13 @@ def oracle_run(c, K):
     h = protocol.Hop(c["in_nbrs"], c["W"], c["s"], c["b"], K, max_ig=c["max_ig"], skip_on=c["skip_on"],
                      max_skip=c["max_skip"], trigger=c["trigger"], seed=c["seed"],
                      delay_kind=c["delay_kind"], mult=c["mult"], check=False,
-                     max_latency=c.get("max_latency", 1))
+                     max_latency=c.get("max_latency", 1), serial=c.get("serial", False),
+                     notify_ack=c.get("notify_ack", False))
     return h, h.run()
 
 
 def assert_same_schedule(c, sched, h, recs, K):
-    assert sched.n_records == len(recs) and sched.depth == h.D
+    assert sched.n_records == len(recs) and sched.depth == h.slots
     assert sched.stalled == h.stalled and sched.n_jumps == h.n_jumps and sched.late_sends == h.late_sends
     assert list(sched.kind) == [r.kind for r in recs]
     assert list(sched.worker) == [r.worker for r in recs]
@@ -67,9 +75,9 @@ def assert_same_schedule(c, sched, h, recs, K):
     assert np.array_equal(sched.src_weight.view(np.uint32), w_ref.view(np.uint32))   # bit-exact fp32
     assert list(sched.final_iter) == h.Iter
     assert list(sched.finish_time) == [t or 0 for t in h.finish_time]
-    wv = waves.assign_waves(recs, h.N, h.D)
+    wv = waves.assign_waves(recs, h.N, h.slots)
     assert list(sched.wave) == wv
-    assert waves.check_waves(recs, list(sched.wave), h.N, h.D)
+    assert waves.check_waves(recs, list(sched.wave), h.N, h.slots)
     assert sched.n_waves == (max(wv) + 1 if wv else 0)
     order = list(sched.wave_order)
     assert sorted(order) == list(range(len(recs)))
@@ -80,8 +88,8 @@ def assert_same_schedule(c, sched, h, recs, K):
         assert sched.batch == c["batch"]
         for e in random.Random(0).sample(range(len(recs)), min(40, len(recs))):
             r = recs[e]
-            want = rng.batch_rows(c["seed"], r.worker, r.k, c["batch"], c["rows"]) if r.kind == 0 \
-                else np.zeros(c["batch"], np.int64)
+            want = rng.batch_rows(c["seed"], r.worker, r.k, c["batch"], c["rows"]) \
+                if r.kind in (protocol.STEP, protocol.APPLY) else np.zeros(c["batch"], np.int64)
             assert np.array_equal(sched.batch_rows[e], want)
 
 
@@ -119,6 +127,42 @@ def test_schedule_is_bit_exact_in_random_modes():
         hop.hop_destroy(ctx)
 
 
+def test_serial_and_notify_ack_schedules_are_bit_exact():
+    """The two comparison options (Sections 3.2 and 3.3) in the library's simulator against the oracle: record
+    kinds, times, slots (the serial approach's current-parameter slot included), weights, waves, minibatches,
+    stalls with frozen workers."""
+    rnd = random.Random(23)
+    graphs = [inputs.ring(5), inputs.torus(3, 3), inputs.complete(4),
+              inputs.ring_with_chords(8, 1, 11), inputs.directed_cycle([0, 3, 1, 4, 2])]
+    kinds = set()
+    for trial in range(60):
+        nb = rnd.choice(graphs)
+        serial = trial % 2 == 0
+        s = rnd.choice([0, 0, 1, 3]) if serial else 0
+        b = rnd.randrange(0, min(len(l) for l in nb)) if serial else 0
+        c = dict(in_nbrs=nb, W=inputs.uniform_weights(nb), N=len(nb), d=8, s=s, b=b,
+                 max_ig=rnd.choice([0, 0, 2, 5]), skip_on=serial and rnd.random() < 0.5,
+                 max_skip=rnd.choice([2, 10]), trigger=rnd.choice([0, 1]), lr=0.1, lam=0.0,
+                 batch=rnd.choice([0, 4]), rows=37, seed=500 + trial, delay_kind=rnd.choice([0, 1, 2]),
+                 mult=[rnd.choice([1.0, 1.0, 2.5, float(1 << 62)]) if rnd.random() < 0.3 else 1.0 for _ in nb],
+                 serial=serial, notify_ack=not serial)
+        ctx = host_ctx(c)
+        sched = hop.hop_simulate(ctx, 12, c["delay_kind"], c["mult"])
+        h, recs = oracle_run(c, 12)
+        assert_same_schedule(c, sched, h, recs, 12)
+        kinds.update(r.kind for r in recs)
+        sched.free()
+        hop.hop_destroy(ctx)
+    assert kinds == {protocol.STEP, protocol.JUMP, protocol.APPLY, protocol.REDUCE}
+    # NOTIFY-ACK with anything it cannot support is refused
+    nb = inputs.ring(4)
+    row_ptr, col = inputs.to_csr(nb)
+    for kw, s, b in ((dict(), 1, 0), (dict(), 0, 1), (dict(skip_on=True), 0, 0), (dict(serial=True), 0, 0),
+                     (dict(max_latency=5), 0, 0)):
+        o = hop.make_opts(notify_ack=True, **kw)
+        assert code(lambda: hop.hop_init(row_ptr, col, inputs.uniform_weights(nb), 4, 8, s, b, o)) == hop.HOP_ERR_INVALID_ARG
+
+
 def test_delay_table_and_frozen_worker_stall():
     nb = inputs.complete(3)
     c = dict(in_nbrs=nb, W=inputs.uniform_weights(nb), N=3, d=4, s=0, b=1, max_ig=2, skip_on=False,
@@ -142,10 +186,6 @@ def test_argument_checking():
     W = inputs.uniform_weights(nb)
     o = hop.make_opts()
 
-    def code(fn):
-        with pytest.raises(hop.HopError) as e:
-            fn()
-        return e.value.code
     assert code(lambda: hop.hop_init(row_ptr, col, W, 4, 8, 1, 2, o)) == hop.HOP_ERR_BAD_BACKUP
     bad = col.copy()
     bad[0] = 0                                             # self edge at node 0
