@@ -44,9 +44,9 @@ enum {
     HOP_OK = 0,
     HOP_ERR_INVALID_ARG = -1,     /* null pointer, negative size, unknown enum value */
     HOP_ERR_BAD_GRAPH = -2,       /* index out of range, self edge, unsorted or duplicate neighbour,
-                                     degree + 1 > HOP_MAX_A */
+                                     degree + 1 > HOP_MAX_A, or not strongly connected (Theorems 1 and 2) */
     HOP_ERR_BAD_WEIGHTS = -3,     /* negative weight, weight on a non-edge, zero self weight, or a
-                                     receiver's column not summing to 1 within 1e-4 (Section 3.1) */
+                                     receiver's column not summing to 1 within 1e-6 (Section 3.1) */
     HOP_ERR_BAD_BACKUP = -4,      /* b >= |N_in(i)| for some i (backup-worker figure: N_buw < |N_in|) */
     HOP_ERR_ARENA_TOO_SMALL = -5,
     HOP_ERR_DEADLOCK = -6,        /* events ran out with unfinished workers; the schedule of what

@@ -16,10 +16,11 @@ Modules
   waves     level schedule of records over ring slots + its validity check
   brute     exhaustive untimed enumeration of the protocol for tiny graphs
 
-Parity pins (tests/test_oracle_*.py): closed form X_{k+1} = W^T X_k - eta G_k,
-matrix powers, eigenvalue contraction, Theorem 1 / Theorem 2 bounds, the token
-identity, the paper's worked examples, Eq. 2 by hand, numpy matmul gradient,
-finite differences, exhaustive enumeration.  Unpinned readings (the paper gives
-no algorithm): the hybrid accept rule (backup workers together with staleness)
-and the skip trigger; both are checked by invariants only.
+Parity pins (tests/test_oracle_*.py, tests/test_next_*.py): closed forms X_{k+1} = W^T X_k - eta G_k (parallel
+approach) and X_{k+1} = W^T (X_k - eta G_k) (serial approach), matrix powers, eigenvalue contraction, Theorem 1 /
+Theorem 2 bounds, the token identity, the iteration-gap table (NOTIFY-ACK row included), the paper's worked
+examples, Eq. 2 by hand, numpy matmul gradient, finite differences, exhaustive enumeration.  Two readings the
+paper gives no algorithm for - the hybrid accept rule (backup workers together with staleness) and the skip
+trigger / size - are pinned by traces worked by hand under those readings (tests/golden/hybrid_trace.txt,
+jump_trace.txt); they remain readings, stated in the repository's design notes.
 """

@@ -88,17 +88,25 @@ size_t workspace_need(size_t R, size_t B) {
 
 // Pack the Reduce jobs of one wave two by two: a record is joined with the later record (among the next 64 still
 // single) that shares the most sources with it, provided the union stays within HOP_PAIR_U vectors.  Union order:
-// the first record's sources in its own order, then what the second adds.  Returns the distinct vectors of the wave.
+// the first record's sources in its own order, then what the second adds.  Only waves whose records read every
+// distinct vector at least twice on average are paired: there a shared load in registers saves an L2 request that
+// matters (32 workers, 23 records of ~7 sources per wave: 1472 -> 1434 us per launch); where records share little
+// (64 workers, 9 records of ~5 sources per wave) single records run 3 % faster than pairs, which halve the number
+// of workgroups per column chunk without saving many loads.  Returns the distinct vectors of the wave.
 int pack_pairs(const HopMixJob* jobs, int n, std::vector<HopPairJob>& out) {
     std::vector<char> used((size_t)n, 0);
     std::vector<const float*> all;
+    for (int i = 0; i < n; ++i) all.insert(all.end(), jobs[i].src, jobs[i].src + jobs[i].A);
+    const size_t reads = all.size();
+    std::sort(all.begin(), all.end());
+    const int distinct = (int)(std::unique(all.begin(), all.end()) - all.begin());
+    const bool pairing = reads >= 2 * (size_t)distinct;
     for (int i = 0; i < n; ++i) {
-        all.insert(all.end(), jobs[i].src, jobs[i].src + jobs[i].A);
         if (used[i]) continue;
         used[i] = 1;
         const HopMixJob& a = jobs[i];
         int best = -1, best_overlap = 0;
-        if (a.A <= HOP_PAIR_U) {
+        if (pairing && a.A <= HOP_PAIR_U) {
             int seen = 0;
             for (int k = i + 1; k < n && seen < 64; ++k) {
                 if (used[k]) continue;
@@ -140,8 +148,7 @@ int pack_pairs(const HopMixJob* jobs, int n, std::vector<HopPairJob>& out) {
         }
         out.push_back(pj);
     }
-    std::sort(all.begin(), all.end());
-    return (int)(std::unique(all.begin(), all.end()) - all.begin());
+    return distinct;
 }
 
 float* slot_ptr(const hop_ctx* c, int worker, int slot) {
@@ -453,6 +460,22 @@ static int init_ctx(hop_ctx** out, const hop_graph* g, const float* W, int32_t N
             for (int j : c->in_nbrs[i]) c->out_nbrs[j].push_back(i);   // ascending by construction
         for (int i = 0; i < N; ++i)
             if (b > 0 && b >= (int)c->in_nbrs[i].size()) rc = HOP_ERR_BAD_BACKUP;
+        // the bounds of Theorems 1 and 2 need a path from every node to every other one: everything must be
+        // reachable from node 0 along the edges and against them
+        for (int dir = 0; dir < 2 && rc == HOP_OK; ++dir) {
+            const auto& adj = dir == 0 ? c->out_nbrs : c->in_nbrs;
+            std::vector<char> seen((size_t)N, 0);
+            std::vector<int> stack{0};
+            seen[0] = 1;
+            int reached = 1;
+            while (!stack.empty()) {
+                int u = stack.back();
+                stack.pop_back();
+                for (int v : adj[u])
+                    if (!seen[v]) { seen[v] = 1; ++reached; stack.push_back(v); }
+            }
+            if (reached != N) rc = HOP_ERR_BAD_GRAPH;
+        }
     }
     if (rc == HOP_OK) {
         c->W.assign(W, W + (size_t)N * N);
@@ -465,7 +488,7 @@ static int init_ctx(hop_ctx** out, const hop_graph* g, const float* W, int32_t N
                 if (!edge && v != 0.f) rc = HOP_ERR_BAD_WEIGHTS;
                 col_sum += v;
             }
-            if (!(W[(size_t)i * N + i] > 0.f) || std::fabs(col_sum - 1.0) > 1e-4) rc = HOP_ERR_BAD_WEIGHTS;
+            if (!(W[(size_t)i * N + i] > 0.f) || std::fabs(col_sum - 1.0) > 1e-6) rc = HOP_ERR_BAD_WEIGHTS;
         }
     }
     if (rc == HOP_OK && dev) {
@@ -701,7 +724,7 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
             // reduced vectors in place: two dependent launches per wave, not three.  Timed as gradient work.
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w] + s->wave_mix_bytes[w]))) return rc;
             if (pj)
-                HOP_LAUNCH(c, hopk_pair_dense_margin(pj, np, s->wave_sources[w], c->d, gj, ng, B, stream));
+                HOP_LAUNCH(c, hopk_pair_dense_margin(pj, np, s->wave_sources[w], w & 1, c->d, gj, ng, B, stream));
             else
                 HOP_LAUNCH(c, hopk_mix_dense_margin(s->mix_dev + jb, nj, c->d, gj, ng, B, stream));
             HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, c->opts.loss, stream));
@@ -716,11 +739,11 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
         const bool csr = ng > 0 && mode == HOP_GRAD_SVM_CSR;
         if (timed && (rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
         if (csr && pj)   // margins and Reduce + Apply both only read x_k: one launch
-            HOP_LAUNCH(c, hopk_pair_csr_margin(pj, np, s->wave_sources[w], c->d, gj, ng, B, c->opts.loss, stream));
+            HOP_LAUNCH(c, hopk_pair_csr_margin(pj, np, s->wave_sources[w], w & 1, c->d, gj, ng, B, c->opts.loss, stream));
         else if (csr)
             HOP_LAUNCH(c, hopk_mix_csr_margin(s->mix_dev + jb, nj, c->d, gj, ng, B, c->opts.loss, stream));
         else if (pj)
-            HOP_LAUNCH(c, hopk_pair(pj, np, s->wave_sources[w], c->d, stream));
+            HOP_LAUNCH(c, hopk_pair(pj, np, s->wave_sources[w], w & 1, c->d, stream));
         else
             HOP_LAUNCH(c, hopk_mix(s->mix_dev + jb, nj, c->d, stream));
         if (timed && (rc = prof_end(c))) return rc;
@@ -893,7 +916,7 @@ int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* stream) {
     int rc = 0;
     if (e == hipSuccess)
         rc = any_vel ? hopk_mix((const HopMixJob*)dev, n_jobs, d, stream)
-                     : hopk_pair((const HopPairJob*)dev, (int)pairs.size(), n_sources, d, stream);
+                     : hopk_pair((const HopPairJob*)dev, (int)pairs.size(), n_sources, 0, d, stream);
     hipError_t e2 = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(dev);
     if (e != hipSuccess) return hip_fail(nullptr, e, "hipMemcpy");

@@ -68,11 +68,12 @@ int hopk_mix_dense_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const 
                           void* stream);
 int hopk_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const HopGradJob* grad_dev, int n_grad, int B,
                         int loss, void* stream);
-int hopk_pair(const HopPairJob* jobs_dev, int n_jobs, int n_sources, int64_t d, void* stream);
-int hopk_pair_csr_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int64_t d, const HopGradJob* grad_dev,
-                         int n_grad, int B, int loss, void* stream);
-int hopk_pair_dense_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int64_t d, const HopGradJob* grad_dev,
-                           int n_grad, int B, void* stream);
+// n_sources: distinct vectors the jobs read (sizes the XCD runs); reverse: walk the vectors from their end
+int hopk_pair(const HopPairJob* jobs_dev, int n_jobs, int n_sources, int reverse, int64_t d, void* stream);
+int hopk_pair_csr_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int reverse, int64_t d,
+                         const HopGradJob* grad_dev, int n_grad, int B, int loss, void* stream);
+int hopk_pair_dense_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int reverse, int64_t d,
+                           const HopGradJob* grad_dev, int n_grad, int B, void* stream);
 int hopk_csr_scatter(const HopGradJob* jobs_dev, int n_jobs, int B, float factor, int into_velocity, void* stream);
 int hopk_csr_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, void* stream);
 int hopk_csr_check(const int64_t* rowptr, const int32_t* col, int64_t rows, int64_t first, int64_t nnz, int64_t d,

@@ -422,7 +422,7 @@ __device__ __forceinline__ void pair_tile_wide(const HopPairJob* __restrict__ jo
 
 // Work of one workgroup; `bid` is its index among the launch's mix workgroups.
 __device__ __forceinline__ void pair_block(const HopPairJob* __restrict__ jobs, int n_jobs, int64_t d, int64_t n_chunks,
-                                           int run, int64_t bid) {
+                                           int run, int reverse, int64_t bid) {
     const int xcd = (int)(bid % kXcd);
     const int64_t local = bid / kXcd;
     const int sub = (int)(local % run);
@@ -430,9 +430,10 @@ __device__ __forceinline__ void pair_block(const HopPairJob* __restrict__ jobs, 
     const int64_t round = local / ((int64_t)run * n_jobs);
     const int64_t ahead = (round * kXcd + xcd) * run + sub;
     if (ahead >= n_chunks) return;
-    // vectors are walked from their end: the kernel that wrote the wave's gradients went through them from
-    // the start, so what it wrote last is still in the memory-side cache when this one begins
-    const int64_t chunk = n_chunks - 1 - ahead;
+    // consecutive launches walk the vectors in opposite directions: what the previous kernels wrote or read last
+    // is still in the memory-side cache when the next launch begins there (1453 -> 1430 us per launch with the
+    // gradient generator in between, 386 -> 381 us between launches of small waves)
+    const int64_t chunk = reverse ? n_chunks - 1 - ahead : ahead;
     const HopPairJob* job = jobs + j;
     const int64_t n4 = d >> 2;
     const int64_t first4 = chunk * (int64_t)(kThreads * kPairVec);
@@ -464,8 +465,8 @@ __device__ __forceinline__ void pair_block(const HopPairJob* __restrict__ jobs, 
 }
 
 __global__ __launch_bounds__(kThreads) void pair_mix_kernel(const HopPairJob* __restrict__ jobs, int n_jobs, int64_t d,
-                                                            int64_t n_chunks, int run) {
-    pair_block(jobs, n_jobs, d, n_chunks, run, blockIdx.x);
+                                                            int64_t n_chunks, int run, int reverse) {
+    pair_block(jobs, n_jobs, d, n_chunks, run, reverse, blockIdx.x);
 }
 
 inline int64_t pair_chunks(int64_t d) {
@@ -782,23 +783,23 @@ __global__ __launch_bounds__(kThreads) void mix_csr_margin_kernel(const HopMixJo
 
 // the same two fusions for the paired Reduce + Apply
 __global__ __launch_bounds__(kThreads) void pair_csr_margin_kernel(const HopPairJob* __restrict__ mix_jobs, int n_mix,
-                                                                   int64_t d, int64_t n_chunks, int run,
+                                                                   int64_t d, int64_t n_chunks, int run, int reverse,
                                                                    const HopGradJob* __restrict__ grad_jobs, int B,
                                                                    int rows_per_job_blocks, int loss, int margin_blocks) {
     if ((int)blockIdx.x < margin_blocks) {
         csr_margin_block(grad_jobs, B, rows_per_job_blocks, loss, (int)blockIdx.x);
         return;
     }
-    pair_block(mix_jobs, n_mix, d, n_chunks, run, (int64_t)blockIdx.x - margin_blocks);
+    pair_block(mix_jobs, n_mix, d, n_chunks, run, reverse, (int64_t)blockIdx.x - margin_blocks);
 }
 
 __global__ __launch_bounds__(kThreads) void pair_dense_margin_kernel(const HopPairJob* __restrict__ mix_jobs, int n_mix,
-                                                                     int64_t d, int64_t n_chunks, int run,
+                                                                     int64_t d, int64_t n_chunks, int run, int reverse,
                                                                      const HopGradJob* __restrict__ grad_jobs, int B,
                                                                      int nseg, int64_t margin_blocks) {
     __shared__ float red[kThreads / 64];
     if ((int64_t)blockIdx.x >= margin_blocks) {
-        pair_block(mix_jobs, n_mix, d, n_chunks, run, (int64_t)blockIdx.x - margin_blocks);
+        pair_block(mix_jobs, n_mix, d, n_chunks, run, reverse, (int64_t)blockIdx.x - margin_blocks);
         return;
     }
     dense_margin_block(grad_jobs, B, d, nseg, blockIdx.x, red);
@@ -985,20 +986,20 @@ int hopk_mix_csr_margin(const HopMixJob* mix_dev, int n_mix, int64_t d, const Ho
     return launch_mix_csr_margin<4, 1, 1>(mix_dev, n_mix, d, grad_dev, n_grad, B, loss, stream);
 }
 
-int hopk_pair(const HopPairJob* jobs_dev, int n_jobs, int n_sources, int64_t d, void* stream) {
+int hopk_pair(const HopPairJob* jobs_dev, int n_jobs, int n_sources, int reverse, int64_t d, void* stream) {
     if (n_jobs <= 0) return 0;
     const int64_t n_chunks = pair_chunks(d);
     const int run = pair_run(n_sources, n_chunks);
     const int64_t grid = pair_grid(n_jobs, n_chunks, run);
     if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(pair_mix_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev, n_jobs, d,
-                       n_chunks, run);
+                       n_chunks, run, reverse);
     return launch_status();
 }
 
-int hopk_pair_csr_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int64_t d, const HopGradJob* grad_dev,
-                         int n_grad, int B, int loss, void* stream) {
-    if (n_grad <= 0 || B <= 0) return hopk_pair(mix_dev, n_mix, n_sources, d, stream);
+int hopk_pair_csr_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int reverse, int64_t d,
+                         const HopGradJob* grad_dev, int n_grad, int B, int loss, void* stream) {
+    if (n_grad <= 0 || B <= 0) return hopk_pair(mix_dev, n_mix, n_sources, reverse, d, stream);
     if (n_mix <= 0) return hopk_csr_margin(grad_dev, n_grad, B, loss, stream);
     const int64_t n_chunks = pair_chunks(d);
     const int run = pair_run(n_sources, n_chunks);
@@ -1007,13 +1008,14 @@ int hopk_pair_csr_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, in
     const int64_t margin_blocks = (int64_t)n_grad * per;
     if (grid + margin_blocks > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(pair_csr_margin_kernel, dim3((unsigned)(grid + margin_blocks)), dim3(kThreads), 0,
-                       (hipStream_t)stream, mix_dev, n_mix, d, n_chunks, run, grad_dev, B, per, loss, (int)margin_blocks);
+                       (hipStream_t)stream, mix_dev, n_mix, d, n_chunks, run, reverse, grad_dev, B, per, loss,
+                       (int)margin_blocks);
     return launch_status();
 }
 
-int hopk_pair_dense_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int64_t d, const HopGradJob* grad_dev,
-                           int n_grad, int B, void* stream) {
-    if (n_grad <= 0 || B <= 0) return hopk_pair(mix_dev, n_mix, n_sources, d, stream);
+int hopk_pair_dense_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, int reverse, int64_t d,
+                           const HopGradJob* grad_dev, int n_grad, int B, void* stream) {
+    if (n_grad <= 0 || B <= 0) return hopk_pair(mix_dev, n_mix, n_sources, reverse, d, stream);
     if (n_mix <= 0) return hopk_dense_margin(grad_dev, n_grad, B, d, stream);
     const int64_t n_chunks = pair_chunks(d);
     const int run = pair_run(n_sources, n_chunks);
@@ -1022,7 +1024,7 @@ int hopk_pair_dense_margin(const HopPairJob* mix_dev, int n_mix, int n_sources, 
     const int64_t margin_blocks = (int64_t)n_grad * B * nseg;
     if (grid + margin_blocks > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(pair_dense_margin_kernel, dim3((unsigned)(grid + margin_blocks)), dim3(kThreads), 0,
-                       (hipStream_t)stream, mix_dev, n_mix, d, n_chunks, run, grad_dev, B, nseg, margin_blocks);
+                       (hipStream_t)stream, mix_dev, n_mix, d, n_chunks, run, reverse, grad_dev, B, nseg, margin_blocks);
     return launch_status();
 }
 

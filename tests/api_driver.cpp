@@ -15,9 +15,9 @@ int hopk_dense_grad(const HopGradJob*, int, int, int64_t, float, int, void*) { r
 int hopk_csr_margin(const HopGradJob*, int, int, int, void*) { return 1; }
 int hopk_mix_dense_margin(const HopMixJob*, int, int64_t, const HopGradJob*, int, int, void*) { return 1; }
 int hopk_mix_csr_margin(const HopMixJob*, int, int64_t, const HopGradJob*, int, int, int, void*) { return 1; }
-int hopk_pair(const HopPairJob*, int, int, int64_t, void*) { return 1; }
-int hopk_pair_csr_margin(const HopPairJob*, int, int, int64_t, const HopGradJob*, int, int, int, void*) { return 1; }
-int hopk_pair_dense_margin(const HopPairJob*, int, int, int64_t, const HopGradJob*, int, int, void*) { return 1; }
+int hopk_pair(const HopPairJob*, int, int, int, int64_t, void*) { return 1; }
+int hopk_pair_csr_margin(const HopPairJob*, int, int, int, int64_t, const HopGradJob*, int, int, int, void*) { return 1; }
+int hopk_pair_dense_margin(const HopPairJob*, int, int, int, int64_t, const HopGradJob*, int, int, void*) { return 1; }
 int hopk_csr_scatter(const HopGradJob*, int, int, float, int, void*) { return 1; }
 int hopk_csr_dense_grad(const HopGradJob*, int, int, int64_t, float, void*) { return 1; }
 int hopk_csr_check(const int64_t*, const int32_t*, int64_t, int64_t, int64_t, int64_t, int*, void*) { return 1; }

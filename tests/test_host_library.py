@@ -187,6 +187,13 @@ def test_argument_checking():
     o = hop.make_opts()
 
     assert code(lambda: hop.hop_init(row_ptr, col, W, 4, 8, 1, 2, o)) == hop.HOP_ERR_BAD_BACKUP
+    # two separate pairs, and a one-way chain 0 -> 1 -> 2: no path between every two nodes
+    for nb2 in ([[1], [0], [3], [2]], [[], [0], [1]]):
+        rp2, col2 = inputs.to_csr(nb2)
+        assert code(lambda: hop.hop_init(rp2, col2, inputs.uniform_weights(nb2), len(nb2), 8, 1, 0, o)) == hop.HOP_ERR_BAD_GRAPH
+    off = W.copy()
+    off[0, 0] += 3e-6                                      # a column that sums to 1 + 3e-6
+    assert code(lambda: hop.hop_init(row_ptr, col, off, 4, 8, 1, 0, o)) == hop.HOP_ERR_BAD_WEIGHTS
     bad = col.copy()
     bad[0] = 0                                             # self edge at node 0
     assert code(lambda: hop.hop_init(row_ptr, bad, W, 4, 8, 1, 0, o)) == hop.HOP_ERR_BAD_GRAPH
