@@ -360,11 +360,13 @@ def test_cfg4_full_size_sampled_columns():
 
 
 @pytest.mark.parametrize("cfgn,over,exact", [(1, dict(), True), (4, dict(d=(1 << 14) + 8, K=40), True),
-                                            (3, dict(d=1 << 13, rows=512, K=25), False)])
+                                            (3, dict(d=1 << 13, rows=512, K=25), False),
+                                            (2, dict(d=8192 + 4, rows=512, K=30), True)])
 def test_graph_replay_equals_kernel_by_kernel(cfgn, over, exact):
     """hop_use_graph: the recorded graph is replayed several times, with other GPU work and
     synchronisations in between, and every replay must leave the rings exactly as the same pass run
-    kernel by kernel does (CSR scatters use atomics, so there to rounding)."""
+    kernel by kernel does (CSR scatters use atomics, so there to rounding).  The fourth case has dense
+    minibatches of 4 MB per record, which take the two-launch margin + gradient path."""
     c = inputs.config(cfgn, **over)
     p0, data = make_data(c)
     snaps = {}
