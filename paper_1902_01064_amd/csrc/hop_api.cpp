@@ -185,17 +185,37 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
     // dense minibatches of up to 2 MB per record take the two-launch path of launch_waves (measured: 0.65 -> 0.51 ms
     // per pass at 256 KB, but 31.0 -> 32.9 ms at 32 MB, where the margin pass wants a kernel of its own for occupancy)
     s->dense_in_place = mode == HOP_GRAD_SVM_DENSE && (int64_t)B * c->d * 4 <= kDenseInPlaceBytes;
+    // Larger dense minibatches: margins, then a gradient kernel that also does the Reduce + Apply of its record
+    // (the time is the rows'; a separate mix launch of a few hundred KB per record would only add its start-up,
+    // measured 4 us + gap per wave at 16 workers x 65536 columns).  The wave's mix then only holds the records
+    // without a gradient (jumps).  Their descriptors come first in the wave's range, so both lists are contiguous.
+    const bool dense_fused = mode == HOP_GRAD_SVM_DENSE && !s->dense_in_place;
     std::vector<HopMixJob> mix((size_t)std::max(R, 1));
     std::vector<HopGradJob> grad;
     s->grad_begin.assign(s->n_waves + 1, 0);
+    s->wave_mix_jobs.assign(s->n_waves, 0);
     s->wave_mix_bytes.assign(s->n_waves, 0.0);
     s->wave_grad_bytes.assign(s->n_waves, 0.0);
     const float eta = c->opts.lr;
+    if (R > 0) s->mix_dev = (HopMixJob*)carve((size_t)R * sizeof(HopMixJob));
+    auto has_gradient = [&](int e) {
+        return (s->kind[e] == HOP_STEP || s->kind[e] == HOP_APPLY) && mode != HOP_GRAD_ZERO;
+    };
     for (int w = 0; w < s->n_waves; ++w) {
-        for (int p = s->wave_begin[w]; p < s->wave_begin[w + 1]; ++p) {
+        const int jb = s->wave_begin[w], je = s->wave_begin[w + 1];
+        int n_plain = je - jb;                         // records whose Reduce stays in the wave's mix launch
+        if (dense_fused) {
+            n_plain = 0;
+            for (int p = jb; p < je; ++p) n_plain += has_gradient(s->wave_order[p]) ? 0 : 1;
+        }
+        s->wave_mix_jobs[w] = n_plain;
+        int next_plain = jb, next_fused = jb + n_plain;
+        for (int p = jb; p < je; ++p) {
             const int e = s->wave_order[p];
             const int i = s->worker[e];
-            HopMixJob& mj = mix[p];
+            const bool fused = dense_fused && has_gradient(e);
+            const int pos = !dense_fused ? p : (fused ? next_fused++ : next_plain++);
+            HopMixJob& mj = mix[pos];
             std::memset(&mj, 0, sizeof(mj));
             mj.out = slot_ptr(c, i, s->out_slot[e]);
             mj.eta = eta;
@@ -205,8 +225,7 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                 mj.src[a] = slot_ptr(c, s->src_worker[q], s->src_slot[q]);
                 mj.w[a] = s->src_weight[q];
             }
-            const bool step = s->kind[e] == HOP_STEP || s->kind[e] == HOP_APPLY;     // records that apply a gradient
-            if (step && mode != HOP_GRAD_ZERO) {
+            if (has_gradient(e)) {                     // STEP and APPLY records
                 HopGradJob gj;
                 std::memset(&gj, 0, sizeof(gj));
                 gj.w = mj.src[0];
@@ -222,19 +241,18 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                     gj.X = dd.X;
                     gj.y = dd.y;
                     gj.partial = c->partial + (int64_t)i * partial_floats(c->d, c->opts.batch);
-                    if (s->dense_in_place) {
-                        // the mix only reduces; the gradient kernel applies -eta g (through the velocity, if any)
-                        // to the reduced vector in place, so no dense g is written and read back
-                        gj.out = mj.out;
-                        gj.eta = eta;
-                        if (c->vel) {
-                            gj.vel = c->vel + (int64_t)i * c->stride;
-                            gj.mu = c->opts.momentum;
-                        }
-                        s->wave_grad_bytes[w] += 4.0 * (c->vel ? 2.0 * c->d : 0.0) + 4.0 * c->d;
-                    } else {
-                        mj.g = gj.g;                   // the gradient kernel writes g, the mix applies it
+                    // the gradient kernel applies -eta g (through the velocity, if any) itself, so no dense g is
+                    // written and read back: in place on the vector the mix has reduced (small minibatches), or on
+                    // its own Reduce of the record's sources (large ones)
+                    gj.out = mj.out;
+                    gj.eta = eta;
+                    if (fused) gj.reduce = s->mix_dev + pos;
+                    if (c->vel) {
+                        gj.vel = c->vel + (int64_t)i * c->stride;
+                        gj.mu = c->opts.momentum;
                     }
+                    s->wave_grad_bytes[w] += 4.0 * (c->vel ? 2.0 * c->d : 0.0) + 4.0 * c->d;
+                    if (fused) s->wave_grad_bytes[w] += 4.0 * (double)c->d * mj.A;
                     s->wave_grad_bytes[w] += 4.0 * ((double)B * c->d + 2.0 * c->d) + 8.0 * B;
                 } else if (mode == HOP_GRAD_SVM_CSR) {
                     if (!dd.rowptr || !dd.col || !dd.val || !dd.y) return HOP_ERR_STATE;
@@ -269,14 +287,11 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                     mj.mu = c->opts.momentum;
                 }
             }
-            s->wave_mix_bytes[w] += 4.0 * (double)c->d * (mj.A + 1 + (mj.g ? 1 : 0) + (mj.vel ? 2 : 0));
+            if (!fused) s->wave_mix_bytes[w] += 4.0 * (double)c->d * (mj.A + 1 + (mj.g ? 1 : 0) + (mj.vel ? 2 : 0));
         }
         s->grad_begin[w + 1] = (int32_t)grad.size();
     }
-    if (R > 0) {
-        s->mix_dev = (HopMixJob*)carve((size_t)R * sizeof(HopMixJob));
-        HOP_HIP(c, hipMemcpy(s->mix_dev, mix.data(), (size_t)R * sizeof(HopMixJob), hipMemcpyHostToDevice));
-    }
+    if (R > 0) HOP_HIP(c, hipMemcpy(s->mix_dev, mix.data(), (size_t)R * sizeof(HopMixJob), hipMemcpyHostToDevice));
     // without velocities the Reduce runs on records packed in pairs
     s->pair_begin.assign(s->n_waves + 1, 0);
     s->wave_sources.assign(s->n_waves, 0);
@@ -284,8 +299,7 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
         std::vector<HopPairJob> pairs;
         pairs.reserve((size_t)R);
         for (int w = 0; w < s->n_waves; ++w) {
-            const int jb = s->wave_begin[w], nj = s->wave_begin[w + 1] - jb;
-            s->wave_sources[w] = pack_pairs(mix.data() + jb, nj, pairs);
+            s->wave_sources[w] = pack_pairs(mix.data() + s->wave_begin[w], s->wave_mix_jobs[w], pairs);
             s->pair_begin[w + 1] = (int32_t)pairs.size();
         }
         s->pair_dev = (HopPairJob*)carve((size_t)R * sizeof(HopPairJob));
@@ -708,7 +722,7 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
     const int B = s->batch;
     const int mode = c->grad_mode;
     for (int w = wb; w < we; ++w) {
-        const int jb = s->wave_begin[w], nj = s->wave_begin[w + 1] - jb;
+        const int jb = s->wave_begin[w], nj = s->wave_mix_jobs[w];
         const int gb = s->grad_begin[w], ng = s->grad_begin[w + 1] - gb;
         const HopGradJob* gj = s->grad_dev ? s->grad_dev + gb : nullptr;
         const HopPairJob* pj = s->pair_dev ? s->pair_dev + s->pair_begin[w] : nullptr;   // null: contexts with a velocity
@@ -731,11 +745,13 @@ static int launch_waves(hop_ctx* c, hop_schedule* s, int wb, int we, void* strea
             if (timed && (rc = prof_end(c))) return rc;
             continue;
         } else if (ng > 0 && mode == HOP_GRAD_SVM_DENSE) {
+            // Large minibatches: margins, then gradient + Reduce + Apply of the same records in one kernel.
             if (timed && (rc = prof_begin(c, HOP_KERNEL_GRAD, s->wave_grad_bytes[w]))) return rc;
             HOP_LAUNCH(c, hopk_dense_margin(gj, ng, B, c->d, stream));
             HOP_LAUNCH(c, hopk_dense_grad(gj, ng, B, c->d, c->opts.lambda, c->opts.loss, stream));
             if (timed && (rc = prof_end(c))) return rc;
         }
+        if (nj == 0) continue;                         // every record of the wave was finished by its gradient kernel
         const bool csr = ng > 0 && mode == HOP_GRAD_SVM_CSR;
         if (timed && (rc = prof_begin(c, HOP_KERNEL_MIX, s->wave_mix_bytes[w]))) return rc;
         if (csr && pj)   // margins and Reduce + Apply both only read x_k: one launch

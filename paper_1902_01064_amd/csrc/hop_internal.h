@@ -53,6 +53,8 @@ struct alignas(16) HopGradJob {
                                // applied to it in place (out -= eta g) instead of being written to g
     float* vel;                // with momentum: csr, the velocity the sparse part is scattered into as well;
                                // dense with out set, v <- mu v + g in place and out -= eta v
+    const HopMixJob* reduce;   // dense with out set: if set, out = sum_a w'_a x_a - eta g (the gradient kernel does the
+                               // record's Reduce too); if null, out already holds the reduced vector
     float eta, mu;             // dense with out set
     uint32_t k0, k1, k2;       // synth: hash keys of (seed, worker, iteration)
     float scale;               // synth: fp32 factor
@@ -115,6 +117,8 @@ struct hop_schedule {
     std::vector<int32_t> grad_begin;    // n_waves + 1 offsets into grad_dev
     std::vector<int32_t> pair_begin;    // n_waves + 1 offsets into pair_dev
     std::vector<int32_t> wave_sources;  // distinct vectors each wave reads
+    std::vector<int32_t> wave_mix_jobs; // records in each wave's mix launch (its first descriptors; the rest, if any,
+                                        // are reduced by their gradient kernel)
     std::vector<double> wave_mix_bytes; // algorithmic bytes of each wave's mix launch
     std::vector<double> wave_grad_bytes;
     void* graph_exec = nullptr;         // hipGraphExec_t of waves [0, n_waves), see hop_use_graph()

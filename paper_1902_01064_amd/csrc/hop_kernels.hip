@@ -596,8 +596,8 @@ __device__ __forceinline__ void dense_margin_block(const HopGradJob* __restrict_
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll 4
         for (int64_t i = lo4 + threadIdx.x; i < hi4; i += kThreads) {
-            float4 xv = ld4_stream(x, i);
-            float4 wv = ld4(w, i);
+            float4 xv = ld4(x, i);        // ordinary loads: the gradient pass re-reads the active rows from the
+            float4 wv = ld4(w, i);        // memory-side cache, which non-temporal loads would not fill
             a0 = fmaf(xv.x, wv.x, a0);
             a1 = fmaf(xv.y, wv.y, a1);
             a2 = fmaf(xv.z, wv.z, a2);
@@ -636,7 +636,10 @@ __global__ __launch_bounds__(kThreads) void mix_dense_margin_kernel(const HopMix
 // ----------------------------------------------------- dense SVM: g = lambda w - sum_m c_m x_m ----
 // One workgroup per (job, 1024-column chunk).  The hinge coefficients c_m = y_m / B if
 // y_m <x_m, w> < 1 else 0 are rebuilt by every workgroup from the partial dot products (B values,
-// cheap) and the active rows are compacted in LDS in minibatch order.
+// cheap) and the active rows are compacted in LDS in minibatch order.  Three endings: write g; apply -eta g to
+// a vector the wave's Reduce has already left in the result slot; or do the record's Reduce here as well
+// (steps 2-3 of the standard-training figure on the freshly computed gradient), which saves the launch of a
+// separate mix and the round trip of g through memory when the minibatch is large.
 constexpr int kMaxB = 1024;
 constexpr int kRowUnroll = 8;
 
@@ -686,6 +689,7 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
     const float* w = job->w;
     float* g = job->g;
     float* out = job->out;                             // set: apply -eta g (or -eta v) to it instead of writing g
+    const HopMixJob* red = job->reduce;                // set (with out): out = sum_a w'_a x_a - eta g, the Reduce done here
     float* vel = job->vel;
     const float neg_eta = -job->eta, mu = job->mu;
     if ((d & 3) == 0) {
@@ -711,13 +715,26 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
                                     fmaf(lambda, wv.z, -acc.z), fmaf(lambda, wv.w, -acc.w));
             if (out == nullptr) {
                 st4(g, i, gv);
-            } else {                                   // Apply in place on the reduced vector
+            } else {
                 if (vel != nullptr) {
                     const float4 v = ld4(vel, i);
                     gv = make_float4(fmaf(mu, v.x, gv.x), fmaf(mu, v.y, gv.y), fmaf(mu, v.z, gv.z), fmaf(mu, v.w, gv.w));
                     st4(vel, i, gv);
                 }
-                const float4 o = ld4(out, i);
+                float4 o;
+                if (red != nullptr) {                  // the record's Reduce, in the order the mix kernels sum
+                    const int A = red->A;
+                    float4 v = ld4(red->src[0], i);
+                    float wa = red->w[0];
+                    o = make_float4(wa * v.x, wa * v.y, wa * v.z, wa * v.w);
+                    for (int a = 1; a < A; ++a) {
+                        v = ld4(red->src[a], i);
+                        wa = red->w[a];
+                        o = make_float4(fmaf(wa, v.x, o.x), fmaf(wa, v.y, o.y), fmaf(wa, v.z, o.z), fmaf(wa, v.w, o.w));
+                    }
+                } else {                               // already reduced into the result slot
+                    o = ld4(out, i);
+                }
                 st4(out, i, make_float4(fmaf(neg_eta, gv.x, o.x), fmaf(neg_eta, gv.y, o.y), fmaf(neg_eta, gv.z, o.z),
                                         fmaf(neg_eta, gv.w, o.w)));
             }
@@ -736,7 +753,14 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
                         gv = fmaf(mu, vel[c], gv);
                         vel[c] = gv;
                     }
-                    out[c] = fmaf(neg_eta, gv, out[c]);
+                    float o;
+                    if (red != nullptr) {
+                        o = red->w[0] * red->src[0][c];
+                        for (int a = 1; a < red->A; ++a) o = fmaf(red->w[a], red->src[a][c], o);
+                    } else {
+                        o = out[c];
+                    }
+                    out[c] = fmaf(neg_eta, gv, o);
                 }
             }
         }
