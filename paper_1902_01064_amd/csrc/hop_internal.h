@@ -62,7 +62,7 @@ struct alignas(16) HopGradJob {
 
 // ---- kernel launchers (hop_kernels.hip); all return a hipError_t as int ------------
 int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream);
-int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream);
+int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int reverse, int64_t d, void* stream);
 int hopk_dense_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, void* stream);
 int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, float lambda, int loss, void* stream);
 int hopk_csr_margin(const HopGradJob* jobs_dev, int n_jobs, int B, int loss, void* stream);

@@ -519,11 +519,14 @@ __device__ __forceinline__ float synth_one(uint32_t c, uint32_t k0, uint32_t k1,
 constexpr int kSynthVec = 2;
 constexpr int kSynthChunk4 = kThreads * kSynthVec;
 
+// `reverse`: walk the vectors from their end, so that the launch finishes where the Reduce + Apply that consumes
+// these gradients starts and finds their last-written part still in the memory-side cache.
 __global__ __launch_bounds__(kThreads) void synth_kernel(const HopGradJob* __restrict__ jobs, int n_jobs,
-                                                         int64_t d, int64_t n_chunks) {
+                                                         int64_t d, int64_t n_chunks, int reverse) {
     int j;
     int64_t chunk;
     if (!map_block(blockIdx.x, n_jobs, n_chunks, &j, &chunk)) return;
+    if (reverse) chunk = n_chunks - 1 - chunk;
     const HopGradJob* job = jobs + j;
     const uint32_t k0 = job->k0, k1 = job->k1, k2 = job->k2;
     const float scale = job->scale;
@@ -990,7 +993,7 @@ int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
     return launch_mix<4, 1, 1, 256>(jobs_dev, n_jobs, d, stream);
 }
 
-int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream) {
+int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int reverse, int64_t d, void* stream) {
     if (n_jobs <= 0) return 0;
     int64_t n4 = d >> 2;
     int64_t n_chunks = (n4 + kSynthChunk4 - 1) / kSynthChunk4;
@@ -998,7 +1001,7 @@ int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int64_t d, void* stream) 
     int64_t grid = grid_for(n_jobs, n_chunks);
     if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(synth_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev,
-                       n_jobs, d, n_chunks);
+                       n_jobs, d, n_chunks, reverse);
     return launch_status();
 }
 

@@ -9,7 +9,7 @@
 // The kernel launchers live in the HIP translation unit; a context without device memory never
 // reaches them, so the sanitizer build only needs the symbols.
 int hopk_mix(const HopMixJob*, int, int64_t, void*) { return 1; }
-int hopk_synth(const HopGradJob*, int, int64_t, void*) { return 1; }
+int hopk_synth(const HopGradJob*, int, int, int64_t, void*) { return 1; }
 int hopk_dense_margin(const HopGradJob*, int, int, int64_t, void*) { return 1; }
 int hopk_dense_grad(const HopGradJob*, int, int, int64_t, float, int, void*) { return 1; }
 int hopk_csr_margin(const HopGradJob*, int, int, int, void*) { return 1; }
