@@ -191,8 +191,11 @@ int hop_opts_default(hop_opts* o);
  * (slot D: the worker's current parameters, never sent). */
 int hop_layout(int64_t d, int32_t s, const hop_opts* o, int32_t* depth, int64_t* stride);
 
-/* Bytes of device memory hop_init needs for rings, gradient buffers and scratch. */
-size_t hop_arena_bytes(int32_t N, int64_t d, int32_t s, const hop_opts* o);
+/* Bytes of device memory hop_init needs for rings, gradient buffers and scratch, for the same N, d, s, b and
+ * options as hop_init will be given (backup workers change which updates are averaged, not how many versions
+ * are kept, so b only has to be valid: 0 is returned for b < 0, as for any other argument hop_init would
+ * refuse on sight). */
+size_t hop_arena_bytes(int32_t N, int64_t d, int32_t s, int32_t b, const hop_opts* o);
 
 /* Creates a context.  W is host, N x N row-major, W[j*N + i] = weight of sender j at receiver i
  * (Section 3.1; every receiver's column sums to 1).  s = staleness bound (Section 4.4), b = backup

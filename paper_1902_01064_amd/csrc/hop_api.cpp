@@ -411,10 +411,10 @@ int hop_layout(int64_t d, int32_t s, const hop_opts* o, int32_t* depth, int64_t*
     return HOP_OK;
 }
 
-size_t hop_arena_bytes(int32_t N, int64_t d, int32_t s, const hop_opts* o) {
+size_t hop_arena_bytes(int32_t N, int64_t d, int32_t s, int32_t b, const hop_opts* o) {
     int32_t D = 0;
     int64_t stride = 0;
-    if (N < 1 || hop_layout(d, s, o, &D, &stride) != HOP_OK) return 0;
+    if (N < 1 || b < 0 || hop_layout(d, s, o, &D, &stride) != HOP_OK) return 0;
     int batch = o ? o->batch : 0;
     int64_t floats = (int64_t)N * D * stride + (int64_t)N * stride + (int64_t)N * partial_floats(d, batch);
     if (o && o->momentum > 0.f) floats += (int64_t)N * stride;
@@ -506,7 +506,7 @@ static int init_ctx(hop_ctx** out, const hop_graph* g, const float* W, int32_t N
         }
     }
     if (rc == HOP_OK && dev) {
-        size_t need = hop_arena_bytes(N, d, s, &o);
+        size_t need = hop_arena_bytes(N, d, s, b, &o);
         if (!dev->arena || ((uintptr_t)dev->arena & 255u)) rc = HOP_ERR_INVALID_ARG;
         else if (dev->arena_bytes < need) rc = HOP_ERR_ARENA_TOO_SMALL;
         else {

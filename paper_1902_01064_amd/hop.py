@@ -104,7 +104,7 @@ def load():
         "hop_version": (C.c_int, []),
         "hop_opts_default": (C.c_int, [C.POINTER(hop_opts)]),
         "hop_layout": (C.c_int, [i64, i32, C.POINTER(hop_opts), C.POINTER(i32), C.POINTER(i64)]),
-        "hop_arena_bytes": (C.c_size_t, [i32, i64, i32, C.POINTER(hop_opts)]),
+        "hop_arena_bytes": (C.c_size_t, [i32, i64, i32, i32, C.POINTER(hop_opts)]),
         "hop_init": (C.c_int, [C.POINTER(vp), C.POINTER(hop_graph), _F32P, i32, i64, i32, i32,
                                C.POINTER(hop_opts), C.POINTER(hop_device)]),
         "hop_destroy": (C.c_int, [vp]),
@@ -184,8 +184,8 @@ def hop_layout(d, s, opts):
     return depth.value, stride.value
 
 
-def hop_arena_bytes(N, d, s, opts):
-    return load().hop_arena_bytes(N, d, s, C.byref(opts))
+def hop_arena_bytes(N, d, s, b, opts):
+    return load().hop_arena_bytes(N, d, s, b, C.byref(opts))
 
 
 def hop_init(row_ptr, col, W, N, d, s, b, opts=None, arena_ptr=None, arena_bytes=0, stream=0):

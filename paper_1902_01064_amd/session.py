@@ -19,7 +19,7 @@ class Session:
                                   max_latency=c.get("max_latency", 0), serial=c.get("serial", False),
                                   notify_ack=c.get("notify_ack", False))
         self.N, self.d = c["N"], c["d"]
-        need = hop.hop_arena_bytes(self.N, self.d, c["s"], self.opts)
+        need = hop.hop_arena_bytes(self.N, self.d, c["s"], c["b"], self.opts)
         self.arena = torch.zeros(need // 4, dtype=torch.float32, device=self.dev)
         assert self.arena.data_ptr() % 256 == 0
         self.stream = torch.cuda.current_stream().cuda_stream

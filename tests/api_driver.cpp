@@ -185,7 +185,8 @@ int main() {
     int64_t stride = 0;
     EXPECT(hop_layout(100, 3, nullptr, &depth, &stride) == HOP_OK && depth == 4 && stride == 192);
     EXPECT(hop_layout(0, 3, nullptr, &depth, &stride) == HOP_ERR_INVALID_ARG);
-    EXPECT(hop_arena_bytes(0, 8, 1, nullptr) == 0 && hop_arena_bytes(4, 8, 1, nullptr) > 0);
+    EXPECT(hop_arena_bytes(0, 8, 1, 0, nullptr) == 0 && hop_arena_bytes(4, 8, 1, 0, nullptr) > 0);
+    EXPECT(hop_arena_bytes(4, 8, 1, -1, nullptr) == 0 && hop_arena_bytes(4, 8, 1, 1, nullptr) == hop_arena_bytes(4, 8, 1, 0, nullptr));
     EXPECT(hop_mix(nullptr, 1, 8, nullptr) == HOP_ERR_INVALID_ARG);
     hop_mix_job mj;
     std::memset(&mj, 0, sizeof(mj));

@@ -85,7 +85,7 @@ int main() {
             o.momentum = momentum;
             o.lr = 0.05f;
             const int s = 2, b = 1;
-            size_t need = hop_arena_bytes(N, d, s, &o);
+            size_t need = hop_arena_bytes(N, d, s, b, &o);
             EXPECT(need > 0);
             void* arena = nullptr;
             HIP_OK(hipMalloc(&arena, need));

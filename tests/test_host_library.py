@@ -211,7 +211,7 @@ def test_argument_checking():
     assert code(lambda: hop.hop_set_rows(ctx, 9, 1)) == hop.HOP_ERR_INVALID_ARG
     assert hop.hop_layout(1 << 20, 3, o) == (4, (1 << 20) + 64)
     assert hop.hop_layout(100, 0, hop.make_opts(max_ig=3)) == (5, 192)
-    need = hop.hop_arena_bytes(4, 8, 1, o)
+    need = hop.hop_arena_bytes(4, 8, 1, 0, o)
     assert need >= 4 * (2 + 1) * 8 * 4
     sched.free()
     hop.hop_destroy(ctx)

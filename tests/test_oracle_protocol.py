@@ -41,6 +41,33 @@ def test_delay_draws_are_exp1_and_bernoulli():
     assert rng.duration_ticks(7, rng.DELAY_NONE, 4, NEVER, 0, 0) == rng.TICKS_NEVER
 
 
+def test_delay_and_latency_draws_against_library_distributions():
+    """Whole distributions, not only moments, judged by scipy: Exp(1) durations (Section 7.3.1's random slowdown
+    here; a per-worker factor scales them, Section 7.3.5) by a Kolmogorov-Smirnov test against expon, the
+    flooring to ticks and the multiplier exactly, update latencies and minibatch rows by chi-square tests against
+    the uniform distribution, independence across neighbouring keys by a correlation."""
+    from scipy import stats
+    n = 20000
+    d = np.array([rng.duration_ticks(11, rng.DELAY_EXP1, 16, 1.0, i, k) for i in range(20) for k in range(n // 20)])
+    assert stats.kstest(d / rng.TICKS_PER_UNIT, "expon").pvalue > 1e-3
+    d4 = np.array([rng.duration_ticks(11, rng.DELAY_EXP1, 16, 4.0, i, k) for i in range(20) for k in range(n // 20)])
+    assert np.all(np.abs(d4 - 4 * d) <= 4)                      # same draw, scaled before the floor
+    assert d.min() >= 1 and d.dtype.kind == "i"
+    a = d.reshape(20, -1).astype(float)
+    assert abs(np.corrcoef(a[:, :-1].ravel(), a[:, 1:].ravel())[0, 1]) < 0.03        # successive iterations
+    assert abs(np.corrcoef(a[:-1].ravel(), a[1:].ravel())[0, 1]) < 0.03              # neighbouring workers
+    lat = np.array([rng.latency_ticks(11, 7, s, r, t) for s in range(10) for r in range(10) for t in range(100)])
+    assert lat.min() == 1 and lat.max() == 7
+    assert stats.chisquare(np.bincount(lat)[1:]).pvalue > 1e-3
+    assert rng.latency_ticks(11, 1, 3, 4, 5) == 1 and rng.latency_ticks(11, 0, 3, 4, 5) == 1
+    rows = np.concatenate([rng.batch_rows(11, i, k, 64, 50) for i in range(8) for k in range(20)])
+    assert rows.min() >= 0 and rows.max() == 49
+    assert stats.chisquare(np.bincount(rows, minlength=50)).pvalue > 1e-3
+    six = np.array([rng.duration_ticks(11, rng.DELAY_BERNOULLI6, 8, 1.0, i, k) for i in range(8) for k in range(2500)])
+    k6 = int(np.sum(six == 6 * rng.TICKS_PER_UNIT))
+    assert stats.binomtest(k6, len(six), 1 / 8).pvalue > 1e-3   # 6x slower with probability 1/n
+
+
 # ---- standard mode: Figure "Update Queue" + Theorem 1 -------------------------
 @pytest.mark.parametrize("kind", [rng.DELAY_NONE, rng.DELAY_EXP1, rng.DELAY_BERNOULLI6])
 def test_standard_mode_accepts_every_neighbour_at_tag_k(kind):
