@@ -491,6 +491,20 @@ def test_momentum_and_log_loss(cfgn, over):
     run_parity(inputs.config(cfgn, **over))
 
 
+@pytest.mark.parametrize("over", [
+    dict(d=4099, rows=256, K=16),                              # columns not a multiple of 4: the scalar paths
+    dict(d=4037, batch=130, rows=256, K=16),                   # minibatch not a multiple of the margin kernel's 4 rows
+    dict(d=4098, rows=256, K=16, momentum=0.9),
+    dict(d=4037, batch=131, rows=256, K=12, serial=True),
+])
+def test_large_dense_minibatch_ragged_shapes(over):
+    """Minibatches just above 2 MB per record take the path where the gradient kernel also reduces and applies:
+    ragged column counts and minibatch sizes, with a velocity and with the serial approach."""
+    c = inputs.config(2, **over)
+    assert c["batch"] * c["d"] * 4 > (2 << 20)
+    run_parity(c)
+
+
 def test_data_set_swapped_after_simulate_is_refused():
     """Minibatch ids are drawn for the row counts known to hop_simulate; a smaller data set attached
     afterwards must make hop_step fail instead of reading past its end."""
