@@ -126,6 +126,11 @@ typedef struct {
                                      out-going neighbour has acknowledged update k - 1, sent right after its Reduce;
                                      standard training only (s = 0, b = 0, no skipping, not serial, latency 1),
                                      anything else is HOP_ERR_INVALID_ARG; ring as for max_ig = 2 */
+    int32_t grad_ahead;           /* HOP_GRAD_SYNTH: gradients of this many consecutive waves are generated in
+                                     front of the first of them (0 or 1: wave by wave; at most 16); every
+                                     worker then has that many gradient buffers in the arena.  Same values either
+                                     way; fewer switches between the arithmetic-bound generator and the
+                                     memory-bound Reduce + Apply, which runs slower right after one */
 } hop_opts;
 
 typedef struct {

@@ -21,6 +21,7 @@ struct alignas(16) HopMixJob {
     float w[HOP_MAX_A];
 };
 
+constexpr int kMaxGradAhead = 16;
 constexpr int HOP_PAIR_U = 12;   // most vectors in the union of a pair of records (the kernel unrolls up to this)
 
 // One or two records of a wave whose source sets overlap, run by one workgroup per column chunk: the union of
@@ -158,7 +159,8 @@ struct hop_ctx {
     size_t arena_bytes = 0;
     void* stream = nullptr;
     float* ring = nullptr;              // N x D x stride
-    float* gbuf = nullptr;              // N x stride
+    float* gbuf = nullptr;              // N x grad_ahead x stride
+    int grad_ahead = 1;                 // gradient buffers per worker (hop_opts.grad_ahead, at least 1)
     float* partial = nullptr;           // N x batch x nseg
     float* vel = nullptr;               // N x stride velocities, only with momentum
     std::vector<HopData> data;

@@ -53,7 +53,7 @@ class hop_opts(C.Structure):
                 ("trigger", C.c_int32), ("lr", C.c_float), ("lambda_", C.c_float),
                 ("batch", C.c_int32), ("loss", C.c_int32), ("seed", C.c_uint64),
                 ("momentum", C.c_float), ("max_latency", C.c_uint32), ("serial", C.c_int32),
-                ("notify_ack", C.c_int32)]
+                ("notify_ack", C.c_int32), ("grad_ahead", C.c_int32)]
 
 
 class hop_delay_model(C.Structure):
@@ -160,13 +160,13 @@ def _np_i32(a):
 
 
 def make_opts(max_ig=0, skip_on=False, max_skip=10, trigger=1, lr=0.01, lam=1e-4, batch=0, seed=0,
-              loss=HOP_LOSS_HINGE, momentum=0.0, max_latency=0, serial=False, notify_ack=False):
+              loss=HOP_LOSS_HINGE, momentum=0.0, max_latency=0, serial=False, notify_ack=False, grad_ahead=1):
     o = hop_opts()
     _check(load().hop_opts_default(C.byref(o)), "hop_opts_default")
     o.max_ig, o.skip_on, o.max_skip, o.trigger = int(max_ig), int(bool(skip_on)), int(max_skip), int(trigger)
     o.lr, o.lambda_, o.batch, o.seed = float(lr), float(lam), int(batch), int(seed)
     o.loss, o.momentum, o.max_latency = int(loss), float(momentum), int(max_latency)
-    o.serial, o.notify_ack = int(bool(serial)), int(bool(notify_ack))
+    o.serial, o.notify_ack, o.grad_ahead = int(bool(serial)), int(bool(notify_ack)), int(grad_ahead)
     return o
 
 

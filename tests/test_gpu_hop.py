@@ -505,6 +505,13 @@ def test_large_dense_minibatch_ragged_shapes(over):
     run_parity(c)
 
 
+@pytest.mark.parametrize("ahead", [1, 3, 16])
+def test_gradients_generated_several_waves_ahead(ahead):
+    """hop_opts.grad_ahead: one generator launch for that many waves, a rotating set of gradient buffers per worker.
+    Same records, same values (the per-wave part of run_parity also starts passes in the middle of a group)."""
+    run_parity(inputs.config(4, d=(1 << 13) + 12, K=30, grad_ahead=ahead), strict=True)
+
+
 def test_data_set_swapped_after_simulate_is_refused():
     """Minibatch ids are drawn for the row counts known to hop_simulate; a smaller data set attached
     afterwards must make hop_step fail instead of reading past its end."""

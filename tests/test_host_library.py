@@ -212,6 +212,10 @@ def test_argument_checking():
     assert hop.hop_layout(1 << 20, 3, o) == (4, (1 << 20) + 64)
     assert hop.hop_layout(100, 0, hop.make_opts(max_ig=3)) == (5, 192)
     need = hop.hop_arena_bytes(4, 8, 1, 0, o)
+    ahead = hop.make_opts(grad_ahead=4)
+    depth, stride = hop.hop_layout(8, 1, ahead)
+    assert hop.hop_arena_bytes(4, 8, 1, 0, ahead) == need + 3 * 4 * stride * 4        # three more gradient buffers per worker
+    assert hop.hop_arena_bytes(4, 8, 1, 0, hop.make_opts(grad_ahead=17)) == 0 and hop.hop_arena_bytes(4, 8, 1, 0, hop.make_opts(grad_ahead=-1)) == 0
     assert need >= 4 * (2 + 1) * 8 * 4
     sched.free()
     hop.hop_destroy(ctx)
