@@ -182,8 +182,8 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
                              hipMemcpyHostToDevice));
         HOP_HIP(c, hipMemset(s->coef_dev, 0, (size_t)R * B * sizeof(float)));
     }
-    // dense minibatches of up to 2 MB per record take the two-launch path of launch_waves (measured: 0.65 -> 0.51 ms
-    // per pass at 256 KB, but 31.0 -> 32.9 ms at 32 MB, where the margin pass wants a kernel of its own for occupancy)
+    // dense minibatches of up to 2 MB per record take the margins-beside-the-Reduce path of launch_waves (measured:
+    // 0.65 -> 0.51 ms per pass at 256 KB per record; at 32 MB the margin pass wants a launch of its own for occupancy)
     s->dense_in_place = mode == HOP_GRAD_SVM_DENSE && (int64_t)B * c->d * 4 <= kDenseInPlaceBytes;
     // Larger dense minibatches: margins, then a gradient kernel that also does the Reduce + Apply of its record
     // (the time is the rows'; a separate mix launch of a few hundred KB per record would only add its start-up,
