@@ -18,9 +18,9 @@ class Session:
                                   seed=c["seed"], loss=c.get("loss", 0), momentum=c.get("momentum", 0.0),
                                   max_latency=c.get("max_latency", 0), serial=c.get("serial", False),
                                   notify_ack=c.get("notify_ack", False),
-                                  # synthetic gradients: four waves' worth per generator launch (the mix runs
+                                  # synthetic gradients: eight waves' worth generated back to back (the mix runs
                                   # slower right behind the arithmetic-bound generator), one buffer per wave
-                                  grad_ahead=c.get("grad_ahead", 4 if c["model"] == "synth" else 1))
+                                  grad_ahead=c.get("grad_ahead", 8 if c["model"] == "synth" else 1))
         self.N, self.d = c["N"], c["d"]
         need = hop.hop_arena_bytes(self.N, self.d, c["s"], c["b"], self.opts)
         self.arena = torch.zeros(need // 4, dtype=torch.float32, device=self.dev)
