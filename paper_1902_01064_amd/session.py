@@ -13,14 +13,19 @@ class Session:
         self.c = c
         self.dev = torch.device(device)
         torch.cuda.set_device(self.dev)
+        # synthetic gradients: up to sixteen waves' worth generated back to back (the mix runs slower right behind
+        # the arithmetic-bound generator), one buffer per worker and wave, as far as a quarter of the free memory
+        # (at most 64 GiB) holds them
+        ahead = c.get("grad_ahead", 16 if c["model"] == "synth" else 1)
+        if "grad_ahead" not in c and ahead > 1:
+            room = min(torch.cuda.mem_get_info(self.dev)[0] // 4, 64 << 30)
+            while ahead > 1 and c["N"] * ahead * (c["d"] + 128) * 4 > room:
+                ahead //= 2
         self.opts = hop.make_opts(max_ig=c["max_ig"], skip_on=c["skip_on"], max_skip=c["max_skip"],
                                   trigger=c["trigger"], lr=c["lr"], lam=c["lam"], batch=c["batch"],
                                   seed=c["seed"], loss=c.get("loss", 0), momentum=c.get("momentum", 0.0),
                                   max_latency=c.get("max_latency", 0), serial=c.get("serial", False),
-                                  notify_ack=c.get("notify_ack", False),
-                                  # synthetic gradients: eight waves' worth generated back to back (the mix runs
-                                  # slower right behind the arithmetic-bound generator), one buffer per wave
-                                  grad_ahead=c.get("grad_ahead", 8 if c["model"] == "synth" else 1))
+                                  notify_ack=c.get("notify_ack", False), grad_ahead=ahead)
         self.N, self.d = c["N"], c["d"]
         need = hop.hop_arena_bytes(self.N, self.d, c["s"], c["b"], self.opts)
         self.arena = torch.zeros(need // 4, dtype=torch.float32, device=self.dev)

@@ -505,7 +505,7 @@ def test_large_dense_minibatch_ragged_shapes(over):
     run_parity(c)
 
 
-@pytest.mark.parametrize("ahead", [1, 3, 16])
+@pytest.mark.parametrize("ahead", [1, 3, 8])
 def test_gradients_generated_several_waves_ahead(ahead):
     """hop_opts.grad_ahead: one generator launch for that many waves, a rotating set of gradient buffers per worker.
     Same records, same values (the per-wave part of run_parity also starts passes in the middle of a group)."""
