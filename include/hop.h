@@ -254,9 +254,13 @@ size_t hop_schedule_bytes(const hop_schedule* s);
 int hop_schedule_bind(hop_ctx* ctx, hop_schedule* s, void* workspace, size_t bytes);
 
 /* Enqueues waves [wave_begin, wave_end) of the schedule: per wave the gradient kernels of its STEP
- * records (Compute on x_k, Section 3.2), then one fused Reduce + Apply launch over all its records
- * (with CSR data the margins ride in that launch and the sparse part of the gradient is scattered
- * into the results right after it).  The first call for a schedule (and the first after the gradient
+ * records (Compute on x_k, Section 3.2), then one fused Reduce + Apply launch over all its records.
+ * Variations by gradient source: with CSR data, and with dense minibatches of up to 2 MB per record, the
+ * margins ride in the Reduce launch and the gradient is applied to the results right after it (scattered,
+ * or in place); with larger dense minibatches the gradient kernel itself reduces and applies its record,
+ * and the Reduce launch only holds the records without a gradient; synthetic gradients of up to
+ * hop_opts.grad_ahead consecutive waves are generated in front of the first of them.  The results are the
+ * same in every arrangement up to the rounding of the sums.  The first call for a schedule (and the first after the gradient
  * source or a data set changed) copies the descriptors into the schedule's workspace with synchronous
  * host-to-device copies; after that the call only launches.  Records of one wave touch no
  * ring slot in a conflicting way, so the result equals running the records one by one in schedule
