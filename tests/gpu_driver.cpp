@@ -83,6 +83,7 @@ int main() {
             o.skip_on = 1;
             o.seed = 11;
             o.momentum = momentum;
+            o.grad_ahead = d == 4096 ? 3 : 1;      // synthetic gradients three waves ahead on one of the sizes
             o.lr = 0.05f;
             const int s = 2, b = 1;
             size_t need = hop_arena_bytes(N, d, s, b, &o);
