@@ -705,19 +705,26 @@ __global__ __launch_bounds__(kThreads) void mix_dense_margin_kernel(const HopMix
 constexpr int kMaxB = 1024;
 constexpr int kRowUnroll = 8;
 
-__global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* __restrict__ jobs, int n_jobs,
-                                                              int B, int64_t d, int nseg, float lambda,
-                                                              int loss, int64_t n_chunks) {
+// SPLIT > 1: that many groups of 256 threads share a column chunk and take alternate groups of 8 active rows; their
+// sums are joined through LDS in a fixed order.  For launches that leave most of the GPU idle (4 workers x 1024
+// columns: 4 workgroups), where the time is the chain of dependent row loads: 8 rounds become 2.
+template <int SPLIT>
+__global__ __launch_bounds__(kThreads * SPLIT) void dense_grad_kernel(const HopGradJob* __restrict__ jobs, int n_jobs,
+                                                                      int B, int64_t d, int nseg, float lambda,
+                                                                      int loss, int64_t n_chunks) {
     __shared__ float coefS[kMaxB + kRowUnroll];
     __shared__ int rowS[kMaxB + kRowUnroll];
     __shared__ float allC[kMaxB];
     __shared__ int nactS;
+    __shared__ float4 joinS[SPLIT > 1 ? (SPLIT - 1) * kThreads : 1];
     int j;
     int64_t chunk;
     if (!map_block(blockIdx.x, n_jobs, n_chunks, &j, &chunk)) return;
     const HopGradJob* job = jobs + j;
     const float invB = 1.0f / (float)B;
-    for (int m = threadIdx.x; m < B; m += kThreads) {
+    const int part = SPLIT > 1 ? (int)threadIdx.x / kThreads : 0;     // which share of the rows
+    const int col = SPLIT > 1 ? (int)threadIdx.x % kThreads : (int)threadIdx.x;
+    for (int m = threadIdx.x; m < B; m += kThreads * SPLIT) {
         float dot = 0.f;
         for (int sg = 0; sg < nseg; ++sg) dot += job->partial[(int64_t)m * nseg + sg];
         float c = loss_coef(job->y[job->rows[m]], dot, invB, loss);
@@ -756,10 +763,10 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
     const float neg_eta = -job->eta, mu = job->mu;
     if ((d & 3) == 0) {
         const int64_t n4 = d >> 2;
-        const int64_t i = chunk * kThreads + threadIdx.x;
+        const int64_t i = chunk * kThreads + col;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         if (i < n4) {
-            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int n = 0; n < nact; n += kRowUnroll) {
+            for (int n = part * kRowUnroll; n < nact; n += kRowUnroll * SPLIT) {
                 float4 v[kRowUnroll];
 #pragma unroll
                 for (int u = 0; u < kRowUnroll; ++u) v[u] = ld4(X + (int64_t)rowS[n + u] * d, i);
@@ -772,6 +779,19 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
                     acc.w = fmaf(c, v[u].w, acc.w);
                 }
             }
+        }
+        if (SPLIT > 1) {                               // join the shares: ((part 0 + part 1) + part 2) + ...
+            if (part > 0) joinS[(part - 1) * kThreads + col] = acc;
+            __syncthreads();
+            if (part == 0) {
+#pragma unroll
+                for (int q = 1; q < SPLIT; ++q) {
+                    const float4 t = joinS[(q - 1) * kThreads + col];
+                    acc = make_float4(acc.x + t.x, acc.y + t.y, acc.z + t.z, acc.w + t.w);
+                }
+            }
+        }
+        if (i < n4 && part == 0) {
             float4 wv = ld4(w, i);
             float4 gv = make_float4(fmaf(lambda, wv.x, -acc.x), fmaf(lambda, wv.y, -acc.y),
                                     fmaf(lambda, wv.z, -acc.z), fmaf(lambda, wv.w, -acc.w));
@@ -801,9 +821,9 @@ __global__ __launch_bounds__(kThreads) void dense_grad_kernel(const HopGradJob* 
                                         fmaf(neg_eta, gv.w, o.w)));
             }
         }
-    } else {
+    } else if (part == 0) {
         for (int q = 0; q < 4; ++q) {
-            const int64_t c = (chunk * kThreads + threadIdx.x) * 4 + q;
+            const int64_t c = (chunk * kThreads + col) * 4 + q;
             if (c < d) {
                 float acc = 0.f;
                 for (int n = 0; n < nact; ++n) acc = fmaf(coefS[n], X[(int64_t)rowS[n] * d + c], acc);
@@ -1029,8 +1049,13 @@ int hopk_dense_grad(const HopGradJob* jobs_dev, int n_jobs, int B, int64_t d, fl
     int64_t n_chunks = (d + 4 * kThreads - 1) / (4 * kThreads);
     int64_t grid = grid_for(n_jobs, n_chunks);
     if (grid > 0x7FFFFFFFll) return (int)hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(dense_grad_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev,
-                       n_jobs, B, d, nseg, lambda, loss, n_chunks);
+    // a launch of fewer workgroups than the GPU has CUs is bound by each workgroup's chain of row loads
+    if (grid <= 128 && (d & 3) == 0)
+        hipLaunchKernelGGL(dense_grad_kernel<4>, dim3((unsigned)grid), dim3(kThreads * 4), 0, (hipStream_t)stream,
+                           jobs_dev, n_jobs, B, d, nseg, lambda, loss, n_chunks);
+    else
+        hipLaunchKernelGGL(dense_grad_kernel<1>, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, jobs_dev,
+                           n_jobs, B, d, nseg, lambda, loss, n_chunks);
     return launch_status();
 }
 
