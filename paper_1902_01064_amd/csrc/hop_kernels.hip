@@ -428,7 +428,15 @@ __device__ __forceinline__ void pair_block(const HopPairJob* __restrict__ jobs, 
     const int sub = (int)(local % run);
     const int j = (int)((local / run) % n_jobs);
     const int64_t round = local / ((int64_t)run * n_jobs);
-    const int64_t ahead = (round * kXcd + xcd) * run + sub;
+    int64_t ahead = (round * kXcd + xcd) * run + sub;
+    // the last, partly filled round is dealt out evenly (shorter runs on all XCDs, not full runs on the first few)
+    const int64_t span = (int64_t)kXcd * run;
+    const int64_t done = n_chunks / span * span;
+    if (round * span >= done) {
+        const int tail_run = (int)((n_chunks - done + kXcd - 1) / kXcd);
+        if (sub >= tail_run) return;
+        ahead = done + (int64_t)xcd * tail_run + sub;
+    }
     if (ahead >= n_chunks) return;
     // consecutive launches walk the vectors in opposite directions: what the previous kernels wrote or read last
     // is still in the memory-side cache when the next launch begins there (1453 -> 1430 us per launch with the
