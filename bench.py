@@ -301,6 +301,20 @@ def main():
                     for k in ("mix", "grad", "synth")},
     }
     r = out["roofline"]
+    grad = res["grad"]
+    if grad["ms"] > res["mix"]["ms"] and c["model"] == "dense":
+        # dense SVM configs: the gradient launches (margins; second pass + Reduce + Apply) are the dominant group;
+        # their algorithmic bytes are the minibatch rows once plus the vectors of the record's Reduce and Apply
+        n_g = max(grad["launches"], 1)
+        us = grad["ms"] * 1e3 / n_g
+        out["roofline"] = r = {
+            "bound": "hbm",
+            "kernel": ("dense_margin4_kernel + dense_grad_kernel (one group per wave)" if c["batch"] * c["d"] * 4 > (2 << 20)
+                       else "pair_dense_margin_kernel + dense_grad_kernel (one group per wave; bound by launches)"),
+            "achieved": grad["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": grad["GBps"] / HBM_PEAK_GBS,
+            "traffic": None, "launches": grad["launches"], "avg_launch_us": us,
+            "algorithmic_bytes_per_launch": grad["GBps"] * 1e9 * us * 1e-6,
+        }
     if note:
         r["traffic_note"] = note
     if counters and avg_us > 0:
