@@ -15,6 +15,7 @@ Modules
   arith     weights (Eq. 2 x mixing weights), SVM subgradient, reduce + apply
   waves     level schedule of records over ring slots + its validity check
   brute     exhaustive untimed enumeration of the protocol for tiny graphs
+  brute_na  the same for NOTIFY-ACK (Section 3.3)
 
 Parity pins (tests/test_oracle_*.py, tests/test_next_*.py): closed forms X_{k+1} = W^T X_k - eta G_k (parallel
 approach) and X_{k+1} = W^T (X_k - eta G_k) (serial approach), matrix powers, eigenvalue contraction, Theorem 1 /

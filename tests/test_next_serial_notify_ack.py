@@ -220,3 +220,58 @@ def test_notify_ack_refuses_what_it_cannot_support():
     for kw in (dict(s=1, b=0), dict(s=0, b=1), dict(s=0, b=0, skip_on=True), dict(s=0, b=0, serial=True)):
         with pytest.raises(protocol.ProtocolError):
             protocol.Hop(nb, W, K=3, notify_ack=True, **kw)
+
+
+# ---- NOTIFY-ACK: every interleaving on tiny graphs -----------------------------------------------------
+TINY = {"directed 3-cycle": [[2], [0], [1]], "path of 3": [[1], [0, 2], [1]], "complete 3": [[1, 2], [0, 2], [0, 1]],
+        "one-way edge into a pair": [[1, 2], [0], [1]]}
+
+
+@pytest.mark.parametrize("name", sorted(TINY))
+def test_notify_ack_every_interleaving_on_tiny_graphs(name):
+    """An untimed model of NOTIFY-ACK (oracle/brute_na.py, written from Section 3.3 on its own) walks every
+    interleaving of sends, deliveries, ACKs, Computes and Reduces for 4 iterations: no reachable state is stuck, no
+    edge ever holds two unconsumed updates, and the largest gap Iter(i) - Iter(j) over all reachable states is
+    EXACTLY the table's min(len(j -> i), 2 len(i -> j)) for every ordered pair: the bound holds and is attained."""
+    from scipy.sparse.csgraph import shortest_path
+
+    from oracle import brute_na
+    nb = TINY[name]
+    n = len(nb)
+    A = np.zeros((n, n))
+    for i, l in enumerate(nb):
+        for j in l:
+            A[j, i] = 1
+    dist = shortest_path(A, unweighted=True)
+    states, gap, worst_queue, stuck = brute_na.Model(nb, 4).explore()
+    assert states > 1000 and stuck == 0 and worst_queue == 1
+    for i in range(n):
+        for j in range(n):
+            if i != j:
+                assert gap[i][j] == min(dist[j, i], 2 * dist[i, j]), (name, i, j, gap[i][j])
+
+
+def test_notify_ack_timed_runs_are_walks_of_the_exhaustive_model():
+    """The timed simulator under seeded random delays, multipliers and a table with a very slow worker: the events it
+    shows (enter, Recv, delivery), in order, are one walk of the untimed model, and a trace with two events swapped
+    so that a Recv precedes the delivery it needs is not."""
+    from oracle import brute_na
+    runs = 0
+    for name, nb in sorted(TINY.items()):
+        n = len(nb)
+        W = inputs.uniform_weights(nb)
+        model = brute_na.Model(nb, 4)
+        for seed in range(6):
+            kw = dict(delay_kind=rng.DELAY_EXP1, seed=seed, mult=[1.0 + 3.0 * ((seed + i) % 3 == 0) for i in range(n)])
+            if seed == 5:
+                kw = dict(delay_kind=rng.DELAY_TABLE, table=[[1 + 50 * (i == 0)] * 4 for i in range(n)])
+            h = protocol.Hop(nb, W, 0, 0, 4, notify_ack=True, trace=True, **kw)
+            h.run()
+            assert not h.stalled and model.follows(h.trace), (name, seed)
+            runs += 1
+        bad = list(h.trace)
+        at = next(x for x, ev in enumerate(bad) if ev[0] == "recv")
+        need = max(x for x, ev in enumerate(bad[:at]) if ev[0] == "deliver" and ev[2] == bad[at][1])
+        bad.insert(need, bad.pop(at))                       # the Recv now comes before its last delivery
+        assert not model.follows(bad), name
+    assert runs == 24
