@@ -13,6 +13,8 @@ every such interleaving.  Three kinds of move exist:
   advance(i)     worker i, holding a token from every out-neighbour, removes
                  them and enters the next iteration: inserts its own tokens and
                  Sends (token-queue figure, Section 4.2)
+  send(i)        serial approach of Section 3.2 only: the Send is a move of its own,
+                 any time after entering the iteration and before the Recv
 
 It serves as a pin for the timed simulator: every timed run must be one walk of
 this model, every reachable state must obey the token identity of Theorem 2's
@@ -22,8 +24,9 @@ from collections import deque
 
 
 class Model:
-    def __init__(self, in_nbrs, s, b, K, max_ig=0, skip_on=False, max_skip=10, trigger=1, ordered=True):
+    def __init__(self, in_nbrs, s, b, K, max_ig=0, skip_on=False, max_skip=10, trigger=1, ordered=True, serial=False):
         self.ordered = ordered            # False: any update in flight may arrive next (Section 6.1)
+        self.serial = serial              # True: the serial approach of Section 3.2, Send after Compute and Apply
         self.n = len(in_nbrs)
         self.inn = [tuple(sorted(l)) for l in in_nbrs]
         outn = [[] for _ in in_nbrs]
@@ -37,7 +40,8 @@ class Model:
         self.ig = max_ig if max_ig else max(s, 1)
         self.skip_on, self.max_skip, self.trigger = skip_on, max_skip, trigger
 
-    # state = (it, ph, flight, queue, rcv, tok); ph: 0 running, 1 wants tokens, 2 done
+    # state = (it, ph, flight, queue, rcv, tok); ph: 0 running, 1 wants tokens, 2 done, 3 (serial approach only)
+    # computing with nothing sent yet
     # tok[e] for e = (j, i) is TokenQ(i -> j): kept at i, taken by j.
     def initial(self):
         ne = len(self.edges)
@@ -62,6 +66,8 @@ class Model:
         out.append(("enter", i, k))
         if k >= self.K:
             ph[i] = 2
+        elif self.serial:
+            ph[i] = 3                     # the update of iteration k leaves after Compute and Apply: move "send"
         else:
             ph[i] = 0
             for j in self.outn[i]:
@@ -112,6 +118,8 @@ class Model:
                 mv.append(("fire", i))
             if ph[i] == 1 and all(tok[self.eidx[(i, j)]] >= 1 for j in self.outn[i]):
                 mv.append(("advance", i))
+            if ph[i] == 3:
+                mv.append(("send", i))
         return mv
 
     def apply(self, state, move):
@@ -128,6 +136,12 @@ class Model:
             # staleness mode only ever looks at the newest queued tag
             queue[e] = (max(queue[e] + (tag,)),) if self.s >= 1 else queue[e] + (tag,)
             out.append(("deliver", move[1], move[2], tag))
+        elif move[0] == "send":
+            i = move[1]
+            for j in self.outn[i]:
+                e = self.eidx[(i, j)]
+                flight[e] = flight[e] + (it[i],)
+            ph[i] = 0
         elif move[0] == "fire":
             i = move[1]
             k = it[i]
@@ -198,6 +212,9 @@ class Model:
                 want = pending.popleft()
                 assert want == item, (want, item)
                 continue
+            for i in range(self.n):       # sends leave no trace item and only ever enable other moves: take them at once
+                if state[1][i] == 3:
+                    state, _ = self.apply(state, ("send", i))
             if item[0] == "deliver":
                 mv = ("deliver", item[1], item[2]) if self.ordered else ("deliver", item[1], item[2], item[3])
             elif item[0] == "recv":

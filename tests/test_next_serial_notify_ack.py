@@ -275,3 +275,45 @@ def test_notify_ack_timed_runs_are_walks_of_the_exhaustive_model():
         bad.insert(need, bad.pop(at))                       # the Recv now comes before its last delivery
         assert not model.follows(bad), name
     assert runs == 24
+
+
+# ---- serial approach: every interleaving on tiny graphs -------------------------------------------------
+SERIAL_TINY = [
+    (inputs.ring(4), 0, 0, 3, 1, False),
+    (inputs.directed_cycle([0, 1, 2]), 0, 0, 4, 3, False),
+    (inputs.complete(3), 0, 1, 2, 2, False),
+    (inputs.ring(2), 2, 0, 4, 2, True),
+    (inputs.directed_cycle([0, 1, 2]), 2, 0, 3, 2, True),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SERIAL_TINY)))
+def test_serial_approach_every_interleaving_on_tiny_graphs(case):
+    """The untimed model with the Send as a move of its own after entering an iteration (Section 3.2's serial
+    order): no reachable state is stuck, the token identity, Theorem 2 and the gap table hold in every one, standard
+    mode reduces exactly the tag-k updates of all in-neighbours whatever the interleaving, and every timed serial
+    run is a walk of the model."""
+    from oracle import brute
+    nb, s_, b, K, ig, skip = SERIAL_TINY[case]
+    m = brute.Model(nb, s_, b, K, max_ig=ig, skip_on=skip, serial=True)
+    seen, stuck, fired = m.explore(limit=600_000)
+    assert not stuck and len(seen) > 100
+    for st in seen:
+        it, ph, flight, queue, rcv, tok = st
+        for x, (j, i) in enumerate(m.edges):
+            assert tok[x] == it[i] - it[j] + m.ig and tok[x] >= 0
+            assert it[j] - it[i] <= m.ig
+            if b == 0:
+                assert it[i] - it[j] <= (s_ + 1 if s_ >= 1 else 1)
+    if s_ == 0 and b == 0:
+        for f in fired:
+            assert f[0] == "recv" and f[3] == tuple((j, f[2]) for j in sorted(nb[f[1]]))
+    for seed in range(5):
+        for kind in (rng.DELAY_NONE, rng.DELAY_EXP1):
+            h = protocol.Hop(nb, inputs.uniform_weights(nb), s_, b, K, max_ig=ig, skip_on=skip, seed=seed,
+                             delay_kind=kind, mult=[1.0 + 2.0 * ((seed + i) % 3 == 0) for i in range(len(nb))],
+                             check=True, trace=True, serial=True)
+            h.run()
+            assert not h.stalled
+            end = m.replay(h.trace)
+            assert end in seen and m.final(end)
