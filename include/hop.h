@@ -183,6 +183,7 @@ typedef struct {
     float mu;
 } hop_mix_job;
 
+/* Static text for a HOP_* result code (never NULL); the version of this interface (1). */
 const char* hop_strerror(int code);
 int hop_version(void);
 
@@ -238,6 +239,8 @@ int hop_set_grad_source(hop_ctx* ctx, int mode, float variance, const float* ext
  * `delays` (NULL: one time unit each), and returns the schedule (also when the result is
  * HOP_ERR_DEADLOCK).  Touches no device memory. */
 int hop_simulate(hop_ctx* ctx, const hop_delay_model* delays, int32_t max_iter, hop_schedule** out);
+/* Fills `out` with borrowed pointers to the schedule's host arrays (see hop_schedule_arrays), valid until
+ * hop_schedule_free; HOP_ERR_INVALID_ARG for a NULL argument. */
 int hop_schedule_view(const hop_schedule* s, hop_schedule_arrays* out);
 /* Frees a schedule (host memory only: its device-side descriptors live in the caller's workspace).  A
  * schedule may outlive its context (its host arrays stay valid), but hop_step refuses it once the
