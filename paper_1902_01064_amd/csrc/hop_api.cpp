@@ -86,6 +86,8 @@ size_t workspace_need(size_t R, size_t B) {
            ws_round(R * sizeof(HopGradJob)) + kWsAlign;
 }
 
+}  // namespace
+
 // Pack the Reduce jobs of one wave two by two: a record is joined with the later record (among the next 64 still
 // single) that shares the most sources with it, provided the union stays within HOP_PAIR_U vectors.  Union order:
 // the first record's sources in its own order, then what the second adds.  Only waves whose records read every
@@ -93,7 +95,7 @@ size_t workspace_need(size_t R, size_t B) {
 // matters (32 workers, 23 records of ~7 sources per wave: 1472 -> 1434 us per launch); where records share little
 // (64 workers, 9 records of ~5 sources per wave) single records run 3 % faster than pairs, which halve the number
 // of workgroups per column chunk without saving many loads.  Returns the distinct vectors of the wave.
-int pack_pairs(const HopMixJob* jobs, int n, std::vector<HopPairJob>& out) {
+int hop_pack_pairs(const HopMixJob* jobs, int n, std::vector<HopPairJob>& out) {
     std::vector<char> used((size_t)n, 0);
     std::vector<const float*> all;
     for (int i = 0; i < n; ++i) all.insert(all.end(), jobs[i].src, jobs[i].src + jobs[i].A);
@@ -150,6 +152,8 @@ int pack_pairs(const HopMixJob* jobs, int n, std::vector<HopPairJob>& out) {
     }
     return distinct;
 }
+
+namespace {
 
 float* slot_ptr(const hop_ctx* c, int worker, int slot) {
     return c->ring + ((int64_t)worker * c->slots + slot) * c->stride;
@@ -302,7 +306,7 @@ int build_jobs(hop_ctx* c, hop_schedule* s) {
         std::vector<HopPairJob> pairs;
         pairs.reserve((size_t)R);
         for (int w = 0; w < s->n_waves; ++w) {
-            s->wave_sources[w] = pack_pairs(mix.data() + s->wave_begin[w], s->wave_mix_jobs[w], pairs);
+            s->wave_sources[w] = hop_pack_pairs(mix.data() + s->wave_begin[w], s->wave_mix_jobs[w], pairs);
             s->pair_begin[w + 1] = (int32_t)pairs.size();
         }
         s->pair_dev = (HopPairJob*)carve((size_t)R * sizeof(HopPairJob));
@@ -949,7 +953,7 @@ int hop_mix(const hop_mix_job* jobs, int32_t n_jobs, int64_t d, void* stream) {
     for (const HopMixJob& mj : host) any_vel = any_vel || mj.vel != nullptr;
     std::vector<HopPairJob> pairs;
     int n_sources = 0;
-    if (!any_vel) n_sources = pack_pairs(host.data(), n_jobs, pairs);    // the path hop_step takes without velocities
+    if (!any_vel) n_sources = hop_pack_pairs(host.data(), n_jobs, pairs);    // the path hop_step takes without velocities
     const size_t bytes = any_vel ? host.size() * sizeof(HopMixJob) : pairs.size() * sizeof(HopPairJob);
     void* dev = nullptr;
     HOP_HIP(nullptr, hipMalloc(&dev, bytes));

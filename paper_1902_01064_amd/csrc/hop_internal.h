@@ -61,6 +61,10 @@ struct alignas(16) HopGradJob {
     float scale;               // synth: fp32 factor
 };
 
+// Packs the Reduce jobs of one wave for pair_mix_kernel (appends to `out`; see its definition for the rule); returns the
+// number of distinct vectors the jobs read.  Host only.
+int hop_pack_pairs(const HopMixJob* jobs, int n, std::vector<HopPairJob>& out);
+
 // ---- kernel launchers (hop_kernels.hip); all return a hipError_t as int ------------
 int hopk_mix(const HopMixJob* jobs_dev, int n_jobs, int64_t d, void* stream);
 int hopk_synth(const HopGradJob* jobs_dev, int n_jobs, int reverse, int64_t d, void* stream);

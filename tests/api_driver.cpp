@@ -75,7 +75,68 @@ static long touch(const hop_schedule_arrays& v) {
     return sum;
 }
 
+// Pairing of a wave's Reduce jobs: every record once, unions within the kernel's limit, weights and sources kept.
+static int test_pack_pairs() {
+    std::vector<float> pool(64);
+    unsigned z = 12345;
+    auto rnd = [&z](int n) { z = z * 1664525u + 1013904223u; return (int)((z >> 8) % (unsigned)n); };
+    for (int trial = 0; trial < 200; ++trial) {
+        const int n = 1 + rnd(40), n_src = 2 + rnd(40), max_a = 1 + rnd(trial % 7 == 0 ? HOP_MAX_A : 9);
+        std::vector<HopMixJob> jobs((size_t)n);
+        std::vector<float> outs((size_t)n);
+        size_t reads = 0;
+        std::vector<char> seen((size_t)n_src, 0);
+        for (int i = 0; i < n; ++i) {
+            HopMixJob& j = jobs[(size_t)i];
+            std::memset(&j, 0, sizeof(j));
+            j.out = &outs[(size_t)i];
+            j.eta = 0.5f;
+            j.g = rnd(3) ? &pool[0] : nullptr;
+            j.A = 1 + rnd(max_a);
+            for (int a = 0; a < j.A; ++a) {
+                const int sidx = rnd(n_src);                        // duplicates inside one record may happen
+                j.src[a] = &pool[(size_t)sidx];
+                j.w[a] = 0.125f * (float)(1 + rnd(8));
+                seen[(size_t)sidx] = 1;
+            }
+            reads += (size_t)j.A;
+        }
+        int distinct = 0;
+        for (char c : seen) distinct += c;
+        std::vector<HopPairJob> out;
+        EXPECT(hop_pack_pairs(jobs.data(), n, out) == distinct);
+        std::vector<int> times((size_t)n, 0);
+        bool any_pair = false;
+        for (const HopPairJob& pj : out) {
+            EXPECT(pj.G == 1 || pj.G == 2);
+            EXPECT(pj.U >= 1 && pj.U <= HOP_MAX_A && (pj.G == 1 || pj.U <= HOP_PAIR_U));
+            any_pair = any_pair || pj.G == 2;
+            for (int r = 0; r < pj.G; ++r) {
+                const int i = (int)(pj.out[r] - outs.data());
+                EXPECT(i >= 0 && i < n);
+                ++times[(size_t)i];
+                const HopMixJob& j = jobs[(size_t)i];
+                EXPECT(pj.g[r] == j.g && pj.eta == j.eta);
+                // per distinct vector: what the pair holds for this record (entries switched on) adds up to the
+                // record's own weights on it (a record may list a vector twice), and nothing else is switched on
+                for (size_t v = 0; v < pool.size(); ++v) {
+                    float have = 0.f, want = 0.f;
+                    for (int u = 0; u < pj.U; ++u)
+                        if (pj.src[u] == &pool[v] && (u >= 32 || ((pj.mask[r] >> u) & 1u))) have += pj.w[r][u];
+                    for (int a = 0; a < j.A; ++a)
+                        if (j.src[a] == &pool[v]) want += j.w[a];
+                    EXPECT(have == want);
+                }
+            }
+        }
+        for (int t : times) EXPECT(t == 1);
+        if (reads < 2 * (size_t)distinct) EXPECT(!any_pair);      // records that share little stay single
+    }
+    return 0;
+}
+
 int main() {
+    if (test_pack_pairs() != 0) return 1;
     hop_opts o;
     EXPECT(hop_opts_default(&o) == HOP_OK && hop_opts_default(nullptr) == HOP_ERR_INVALID_ARG);
     EXPECT(std::strcmp(hop_strerror(HOP_ERR_DEADLOCK), "unknown error") != 0 && hop_strerror(-99) != nullptr);
